@@ -1,0 +1,131 @@
+"""ctypes front end of oracle/gqa_oracle.c (test infrastructure only).
+
+Argument marshalling and nothing else: all arithmetic lives in the C file,
+whose header states the definition it follows.  Inputs are numpy arrays of
+bf16 bit patterns (dtype uint16); strides are taken from the arrays, so any
+layout whose last axis is dense can be passed as a view.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "gqa_oracle.c")
+_LIB = os.path.join(_HERE, "libgqa_oracle.so")
+_lib = None
+
+
+class _Shape(ctypes.Structure):
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("num_q_heads", ctypes.c_int32),
+        ("num_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+        ("page_size", ctypes.c_int32), ("block_table_stride", ctypes.c_int32),
+        ("q_stride_b", ctypes.c_int64), ("q_stride_h", ctypes.c_int64),
+        ("k_stride_b", ctypes.c_int64), ("k_stride_h", ctypes.c_int64), ("k_stride_t", ctypes.c_int64),
+        ("v_stride_b", ctypes.c_int64), ("v_stride_h", ctypes.c_int64), ("v_stride_t", ctypes.c_int64),
+        ("scale", ctypes.c_double),
+    ]
+
+
+def build_oracle(force: bool = False) -> str:
+    """Compile the C oracle with gcc (plain -O2, OpenMP for the row loop)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-ffp-contract=off",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build_oracle()
+        _lib = ctypes.CDLL(_LIB)
+        _lib.gqa_oracle_decode_attn.restype = ctypes.c_int
+        _lib.gqa_oracle_decode_attn.argtypes = [
+            ctypes.POINTER(_Shape), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_void_p, ctypes.c_int64, ctypes.c_int]
+    return _lib
+
+
+@dataclass
+class OracleResult:
+    out: np.ndarray                 # [B, Hq, D] float64
+    lse: np.ndarray                 # [B, Hq] float64
+    weights: Optional[np.ndarray]   # [B, Hq, max L] float64 (zero beyond L_b) or None
+    threads: int
+
+
+def _u16(a: np.ndarray) -> np.ndarray:
+    if a.dtype != np.uint16:
+        raise TypeError("bf16 bit patterns must be passed as uint16 arrays")
+    if a.strides[-1] != 2:
+        raise ValueError("last axis must be dense")
+    return a
+
+
+def _base_ptr(a: np.ndarray) -> int:
+    return a.__array_interface__["data"][0]
+
+
+def decode_attn(q: np.ndarray, k: np.ndarray, v: np.ndarray, kv_lens: np.ndarray, scale: float,
+                block_table: Optional[np.ndarray] = None, page_size: int = 0,
+                want_weights: bool = False, threads: Optional[int] = None) -> OracleResult:
+    """q: [B, Hq, D].  Contiguous cache: k, v indexed [b, g, t, d] (any strides,
+    e.g. a transposed view of a token-major array).  Paged cache: k, v indexed
+    [block, g, slot, d] and block_table [B, max_blocks] int32."""
+    lib = _load()
+    q, k, v = _u16(q), _u16(k), _u16(v)
+    B, Hq, D = q.shape
+    Hkv = k.shape[1]
+    if k.shape[3] != D or v.shape[3] != D or v.shape[1] != Hkv:
+        raise ValueError("shape mismatch between q, k, v")
+    kv_lens = np.ascontiguousarray(kv_lens, dtype=np.int32)
+    if kv_lens.shape != (B,):
+        raise ValueError("kv_lens must have shape [B]")
+    sh = _Shape()
+    sh.batch, sh.num_q_heads, sh.num_kv_heads, sh.head_dim = B, Hq, Hkv, D
+    sh.page_size = int(page_size)
+    sh.scale = float(scale)
+    sh.q_stride_b, sh.q_stride_h = q.strides[0] // 2, q.strides[1] // 2
+    sh.k_stride_b, sh.k_stride_h, sh.k_stride_t = (x // 2 for x in k.strides[:3])
+    sh.v_stride_b, sh.v_stride_h, sh.v_stride_t = (x // 2 for x in v.strides[:3])
+    bt_ptr = None
+    if page_size:
+        if block_table is None:
+            raise ValueError("paged cache needs a block table")
+        block_table = np.ascontiguousarray(block_table, dtype=np.int32)
+        sh.block_table_stride = block_table.shape[1]
+        bt_ptr = _base_ptr(block_table)
+        need = -(-int(kv_lens.max(initial=0)) // page_size)
+        if need > block_table.shape[1]:
+            raise ValueError("block table too narrow for kv_lens")
+        for b in range(B):
+            nb = -(-int(kv_lens[b]) // page_size)
+            if nb and (block_table[b, :nb].min() < 0 or block_table[b, :nb].max() >= k.shape[0]):
+                raise ValueError("block table entry out of range")
+    else:
+        if int(kv_lens.max(initial=0)) > k.shape[2]:
+            raise ValueError("kv_lens exceeds the cache length")
+    out = np.empty((B, Hq, D), dtype=np.float64)
+    lse = np.empty((B, Hq), dtype=np.float64)
+    w = None
+    wstride = 0
+    if want_weights:
+        wstride = max(int(kv_lens.max(initial=0)), 1)
+        w = np.zeros((B, Hq, wstride), dtype=np.float64)
+    if threads is None:
+        threads = len(os.sched_getaffinity(0))
+    used = lib.gqa_oracle_decode_attn(ctypes.byref(sh), _base_ptr(q), _base_ptr(k), _base_ptr(v),
+                                      _base_ptr(kv_lens), bt_ptr, _base_ptr(out), _base_ptr(lse),
+                                      _base_ptr(w) if w is not None else None, wstride, int(threads))
+    if used < 0:
+        raise ValueError("oracle rejected its arguments")
+    return OracleResult(out=out, lse=lse, weights=w, threads=used)

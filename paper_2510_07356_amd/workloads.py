@@ -1,0 +1,216 @@
+"""Seeded synthetic decode-attention inputs (numpy only).
+
+This module serves both the HIP path's tests/benchmark and the CPU oracle and
+therefore holds none of the method's arithmetic: it draws random numbers,
+rounds them to bf16 bit patterns, lays them out as a KV cache and nothing else.
+
+The workloads stand in for the paper's long reasoning traces (Section 3.3: a
+32B grouped-query model sampled several times per task; Table 3: traces of
+about 6-7 thousand tokens on average; Section 4.1: at most 32,768 tokens).
+The traces themselves are not reproduced; only their shape is: head counts of
+the 32B model (40 query / 8 KV heads of 128) or of the 8B comparands (32 / 8),
+and KV lengths from 512 to 32,768 tokens.
+
+Random streams: numpy PCG64 seeded with the list [seed, stream, sequence];
+stream 0 = lengths, 1 = Q, 2 = K, 3 = V, 4 = outlier positions,
+5 = block permutation.  fp32 normals are rounded to bf16 with
+round-to-nearest-even and kept as uint16 bit patterns.
+"""
+from __future__ import annotations
+
+import math
+import os
+from concurrent.futures import ThreadPoolExecutor
+from dataclasses import dataclass
+from typing import Optional, Sequence
+
+import numpy as np
+
+BF16_POISON = np.uint16(0x7FC0)   # quiet NaN: any read of padding shows up in the output
+PAGE = 16
+
+_STREAM_LENS, _STREAM_Q, _STREAM_K, _STREAM_V, _STREAM_OUTLIER, _STREAM_PERM = range(6)
+
+
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round-to-nearest-even fp32 -> bf16, returned as uint16 bit patterns."""
+    x = np.asarray(x, dtype=np.float32)
+    u = np.ascontiguousarray(x).reshape(-1).view(np.uint32)
+    r = u + (np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1)))
+    return (r >> np.uint32(16)).astype(np.uint16).reshape(x.shape)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    b = np.asarray(b, dtype=np.uint16)
+    return (b.astype(np.uint32).reshape(-1) << np.uint32(16)).view(np.float32).reshape(b.shape)
+
+
+@dataclass
+class Workload:
+    name: str
+    batch: int
+    num_q_heads: int
+    num_kv_heads: int
+    head_dim: int
+    scale: float
+    page_size: int                      # 0 = contiguous cache
+    q: np.ndarray                       # [B, Hq, D] uint16
+    k: np.ndarray                       # logical index [b|block, g, t|slot, d] uint16 (maybe a strided view)
+    v: np.ndarray
+    kv_lens: np.ndarray                 # [B] int32
+    block_table: Optional[np.ndarray]   # [B, max_blocks] int32, -1 padded, or None
+    layout: str                         # "head_major" or "token_major"
+
+    @property
+    def kv_tokens(self) -> int:
+        return int(self.kv_lens.astype(np.int64).sum())
+
+    @property
+    def kv_bytes(self) -> int:
+        """Algorithmic K+V bytes one attention call has to read."""
+        return self.kv_tokens * 2 * self.num_kv_heads * self.head_dim * 2
+
+    @property
+    def max_kv_len(self) -> int:
+        return int(self.kv_lens.max(initial=0))
+
+
+def _rng(seed: int, stream: int, item: int = 0) -> np.random.Generator:
+    return np.random.default_rng([int(seed), int(stream), int(item)])
+
+
+def _normal_bits(seed: int, stream: int, item: int, shape, row_gain: Optional[np.ndarray] = None) -> np.ndarray:
+    x = _rng(seed, stream, item).standard_normal(shape, dtype=np.float32)
+    if row_gain is not None:            # shape [tokens]: scale whole key positions before rounding
+        x *= row_gain[None, :, None]
+    return f32_to_bf16_bits(x)
+
+
+def _pool() -> ThreadPoolExecutor:
+    return ThreadPoolExecutor(max_workers=max(1, min(16, len(os.sched_getaffinity(0)))))
+
+
+def _as_layout(a_head_major: np.ndarray, layout: str) -> np.ndarray:
+    """Return an array whose logical index is [b, g, t, d]; for token_major the
+    memory order is [b, t, g, d] and the result is a strided view of it."""
+    if layout == "head_major":
+        return a_head_major
+    if layout == "token_major":
+        return np.ascontiguousarray(a_head_major.transpose(0, 2, 1, 3)).transpose(0, 2, 1, 3)
+    raise ValueError(layout)
+
+
+def make_contiguous(name: str, seed: int, batch: int, num_q_heads: int, num_kv_heads: int,
+                    kv_lens: Sequence[int], head_dim: int = 128, cache_len: Optional[int] = None,
+                    layout: str = "head_major", outlier_fraction: float = 0.0,
+                    outlier_gain: float = 8.0, scale: Optional[float] = None) -> Workload:
+    kv_lens = np.asarray(kv_lens, dtype=np.int32)
+    assert kv_lens.shape == (batch,)
+    lmax = int(cache_len if cache_len is not None else max(int(kv_lens.max(initial=0)), 1))
+    D, Hkv = head_dim, num_kv_heads
+    q = _normal_bits(seed, _STREAM_Q, 0, (batch, num_q_heads, D))
+    k = np.full((batch, Hkv, lmax, D), BF16_POISON, dtype=np.uint16)
+    v = np.full((batch, Hkv, lmax, D), BF16_POISON, dtype=np.uint16)
+
+    def fill(b: int) -> None:
+        L = int(kv_lens[b])
+        if L == 0:
+            return
+        gain = None
+        if outlier_fraction > 0.0:
+            n_out = int(round(outlier_fraction * L))
+            pos = _rng(seed, _STREAM_OUTLIER, b).choice(L, size=n_out, replace=False)
+            gain = np.ones(L, dtype=np.float32)
+            gain[pos] = outlier_gain
+        k[b, :, :L, :] = _normal_bits(seed, _STREAM_K, b, (Hkv, L, D), gain)
+        v[b, :, :L, :] = _normal_bits(seed, _STREAM_V, b, (Hkv, L, D))
+
+    with _pool() as ex:
+        list(ex.map(fill, range(batch)))
+    return Workload(name, batch, num_q_heads, Hkv, D,
+                    float(np.float32(scale if scale is not None else 1.0 / math.sqrt(D))), 0,
+                    q, _as_layout(k, layout), _as_layout(v, layout), kv_lens, None, layout)
+
+
+def make_paged(name: str, seed: int, batch: int, num_q_heads: int, num_kv_heads: int,
+               kv_lens: Sequence[int], head_dim: int = 128, page_size: int = PAGE,
+               table_width: Optional[int] = None, spare_blocks: int = 3,
+               layout: str = "head_major", permute: bool = True,
+               scale: Optional[float] = None) -> Workload:
+    """Paged cache: the blocks of all sequences live in one shared pool, in an
+    order given by a seeded permutation.  Sequence b's i-th logical block is
+    perm[off_b + i], off_b the running sum of block counts."""
+    kv_lens = np.asarray(kv_lens, dtype=np.int32)
+    assert kv_lens.shape == (batch,)
+    D, Hkv, P = head_dim, num_kv_heads, page_size
+    nblk = -(-kv_lens.astype(np.int64) // P)
+    total = int(nblk.sum())
+    off = np.concatenate([[0], np.cumsum(nblk)]).astype(np.int64)
+    pool_blocks = total + spare_blocks
+    perm = _rng(seed, _STREAM_PERM).permutation(pool_blocks)[:total] if permute \
+        else np.arange(total, dtype=np.int64)
+    width = int(table_width if table_width is not None else max(int(nblk.max(initial=0)), 1))
+    table = np.full((batch, width), -1, dtype=np.int32)
+    q = _normal_bits(seed, _STREAM_Q, 0, (batch, num_q_heads, D))
+    kp = np.full((pool_blocks, Hkv, P, D), BF16_POISON, dtype=np.uint16)
+    vp = np.full((pool_blocks, Hkv, P, D), BF16_POISON, dtype=np.uint16)
+
+    def fill(b: int) -> None:
+        L, nb = int(kv_lens[b]), int(nblk[b])
+        if L == 0:
+            return
+        blocks = perm[off[b]:off[b] + nb]
+        table[b, :nb] = blocks
+        for pool, stream in ((kp, _STREAM_K), (vp, _STREAM_V)):
+            padded = np.full((Hkv, nb * P, D), BF16_POISON, dtype=np.uint16)
+            padded[:, :L, :] = _normal_bits(seed, stream, b, (Hkv, L, D))
+            pool[blocks] = padded.reshape(Hkv, nb, P, D).transpose(1, 0, 2, 3)
+
+    with _pool() as ex:
+        list(ex.map(fill, range(batch)))
+    if layout == "token_major":      # memory order [block, slot, g, d], logical view unchanged
+        kp = np.ascontiguousarray(kp.transpose(0, 2, 1, 3)).transpose(0, 2, 1, 3)
+        vp = np.ascontiguousarray(vp.transpose(0, 2, 1, 3)).transpose(0, 2, 1, 3)
+    elif layout != "head_major":
+        raise ValueError(layout)
+    return Workload(name, batch, num_q_heads, Hkv, D,
+                    float(np.float32(scale if scale is not None else 1.0 / math.sqrt(D))), P,
+                    q, kp, vp, kv_lens, table, layout)
+
+
+# ---------------------------------------------------------------------------
+# The five named configurations
+# ---------------------------------------------------------------------------
+
+def ragged_lengths(seed: int, batch: int, lo: int, hi: int) -> np.ndarray:
+    """Uniform integers on [lo, hi], both ends included."""
+    return _rng(seed, _STREAM_LENS).integers(lo, hi + 1, size=batch).astype(np.int32)
+
+
+def lognormal_lengths(seed: int, batch: int, median: float, sigma: float, cap: int) -> np.ndarray:
+    """exp(ln median + sigma z), z ~ N(0,1), rounded and clipped to [1, cap]."""
+    z = _rng(seed, _STREAM_LENS).standard_normal(batch)
+    return np.clip(np.rint(np.exp(math.log(median) + sigma * z)), 1, cap).astype(np.int32)
+
+
+CONFIG_NAMES = ("single_seq_512", "uniform_b16_4096", "ragged_b64_1k_16k",
+                "long_b8_32k_outliers", "paged_b128_lognormal")
+
+
+def make_config(index: int, layout: str = "head_major") -> Workload:
+    """index 0..4, in the order of CONFIG_NAMES."""
+    if index == 0:
+        return make_contiguous(CONFIG_NAMES[0], 0, 1, 40, 8, [512], layout=layout)
+    if index == 1:
+        return make_contiguous(CONFIG_NAMES[1], 1, 16, 40, 8, [4096] * 16, layout=layout)
+    if index == 2:
+        lens = ragged_lengths(2, 64, 1024, 16384)
+        return make_contiguous(CONFIG_NAMES[2], 2, 64, 40, 8, lens, cache_len=16384, layout=layout)
+    if index == 3:
+        return make_contiguous(CONFIG_NAMES[3], 3, 8, 40, 8, [32768] * 8, layout=layout,
+                               outlier_fraction=0.001, outlier_gain=8.0)
+    if index == 4:
+        lens = lognormal_lengths(4, 128, 6000.0, 0.6, 32768)
+        return make_paged(CONFIG_NAMES[4], 4, 128, 32, 8, lens, table_width=32768 // PAGE,
+                          layout=layout)
+    raise IndexError(index)

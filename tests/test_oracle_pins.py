@@ -1,0 +1,365 @@
+"""Pins for the fp64 oracle: nothing here re-uses the oracle's own code.
+
+Each test fixes the oracle to something the definition of softmax attention
+(or plain mathematics) determines on its own: brute force in pure Python on
+tiny inputs, closed forms, a hand-derived worked example, invariants, and a
+float64 library routine as a third opinion.  The set is chosen so that a
+dropped term, a wrong sign, a wrong head/group index, a transposed operand or
+a wrong stride/page computation fails at least one of them.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import decode_attn
+from paper_2510_07356_amd.workloads import (BF16_POISON, bf16_bits_to_f32, f32_to_bf16_bits,
+                                           make_contiguous, make_paged)
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def bits(x):
+    """Values that are exactly representable in bf16 -> bit patterns (checked)."""
+    x = np.asarray(x, dtype=np.float32)
+    b = f32_to_bf16_bits(x)
+    assert np.array_equal(bf16_bits_to_f32(b), x), "test value not representable in bf16"
+    return b
+
+
+def small_ints(rng, shape, lo=-4, hi=4, step=0.25):
+    """Random multiples of `step`: exact in bf16, exact products and short sums in fp64."""
+    n = int(round((hi - lo) / step))
+    return (rng.integers(0, n + 1, size=shape) * step + lo).astype(np.float32)
+
+
+def brute_force(q, k, v, lens, scale, group):
+    """Pure-Python softmax attention: exp(s)/sum exp(s) with no maximum
+    subtracted, exactly rounded sums (math.fsum).  q [B][Hq][D]; k, v
+    [B][Hkv][T][D] as nested lists of Python floats."""
+    out, lse, wts = [], [], []
+    for b in range(len(q)):
+        ob, lb, wb = [], [], []
+        for h in range(len(q[b])):
+            g = h // group
+            s = [scale * math.fsum(q[b][h][d] * k[b][g][j][d] for d in range(len(q[b][h])))
+                 for j in range(lens[b])]
+            e = [math.exp(x) for x in s]
+            z = math.fsum(e)
+            w = [x / z for x in e]
+            ob.append([math.fsum(w[j] * v[b][g][j][d] for j in range(lens[b]))
+                       for d in range(len(q[b][h]))])
+            lb.append(math.log(z))
+            wb.append(w)
+        out.append(ob), lse.append(lb), wts.append(wb)
+    return out, lse, wts
+
+
+# --------------------------------------------------------------------------- brute force
+
+@pytest.mark.parametrize("seed,B,Hq,Hkv,D,lens", [
+    (0, 1, 1, 1, 1, [1]),
+    (1, 2, 4, 2, 4, [5, 3]),
+    (2, 2, 6, 2, 3, [1, 4]),
+    (3, 3, 4, 4, 2, [2, 5, 1]),
+    (4, 1, 8, 2, 8, [7]),
+])
+@pytest.mark.parametrize("layout", ["head_major", "token_major"])
+def test_brute_force_contiguous(seed, B, Hq, Hkv, D, lens, layout):
+    rng = np.random.default_rng(seed)
+    T = max(lens) + 2                      # cache longer than any sequence; tail is poison
+    q = small_ints(rng, (B, Hq, D), -2, 2)
+    k = small_ints(rng, (B, Hkv, T, D), -2, 2)
+    v = small_ints(rng, (B, Hkv, T, D))
+    scale = 0.375
+    kb, vb = bits(k), bits(v)
+    for b, L in enumerate(lens):
+        kb[b, :, L:, :] = BF16_POISON
+        vb[b, :, L:, :] = BF16_POISON
+    if layout == "token_major":
+        kb = np.ascontiguousarray(kb.transpose(0, 2, 1, 3)).transpose(0, 2, 1, 3)
+        vb = np.ascontiguousarray(vb.transpose(0, 2, 1, 3)).transpose(0, 2, 1, 3)
+    res = decode_attn(bits(q), kb, vb, np.array(lens), scale, want_weights=True)
+    ref_o, ref_l, ref_w = brute_force(q.tolist(), k.tolist(), v.tolist(), lens, scale, Hq // Hkv)
+    np.testing.assert_allclose(res.out, np.array(ref_o), rtol=0, atol=2e-14)
+    np.testing.assert_allclose(res.lse, np.array(ref_l), rtol=0, atol=2e-14)
+    for b, L in enumerate(lens):
+        np.testing.assert_allclose(res.weights[b, :, :L], np.array(ref_w[b]), rtol=0, atol=1e-15)
+
+
+@pytest.mark.parametrize("layout", ["head_major", "token_major"])
+@pytest.mark.parametrize("page", [2, 4])
+def test_brute_force_paged(layout, page):
+    rng = np.random.default_rng(11)
+    B, Hq, Hkv, D = 3, 4, 2, 4
+    lens = [5, 1, 8]
+    nblk = [-(-L // page) for L in lens]
+    total = sum(nblk)
+    perm = rng.permutation(total + 2)[:total]
+    pool_k = np.full((total + 2, Hkv, page, D), BF16_POISON, dtype=np.uint16)
+    pool_v = pool_k.copy()
+    table = np.full((B, max(nblk) + 1), -1, dtype=np.int32)
+    q = small_ints(rng, (B, Hq, D), -2, 2)
+    k_log = small_ints(rng, (B, Hkv, max(lens), D), -2, 2)
+    v_log = small_ints(rng, (B, Hkv, max(lens), D))
+    off = 0
+    for b, L in enumerate(lens):
+        for i in range(nblk[b]):
+            blk = perm[off + i]
+            table[b, i] = blk
+            for s in range(page):
+                j = i * page + s
+                if j < L:
+                    pool_k[blk, :, s, :] = bits(k_log[b, :, j, :])
+                    pool_v[blk, :, s, :] = bits(v_log[b, :, j, :])
+        off += nblk[b]
+    if layout == "token_major":
+        pool_k = np.ascontiguousarray(pool_k.transpose(0, 2, 1, 3)).transpose(0, 2, 1, 3)
+        pool_v = np.ascontiguousarray(pool_v.transpose(0, 2, 1, 3)).transpose(0, 2, 1, 3)
+    res = decode_attn(bits(q), pool_k, pool_v, np.array(lens), 0.5, block_table=table, page_size=page)
+    ref_o, ref_l, _ = brute_force(q.tolist(), k_log.tolist(), v_log.tolist(), lens, 0.5, Hq // Hkv)
+    np.testing.assert_allclose(res.out, np.array(ref_o), rtol=0, atol=2e-14)
+    np.testing.assert_allclose(res.lse, np.array(ref_l), rtol=0, atol=2e-14)
+
+
+# --------------------------------------------------------------------------- worked example, closed forms
+
+def test_golden_three_keys():
+    rows = {}
+    with open(os.path.join(GOLDEN, "three_keys_ln2.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            key, *vals = line.split()
+            rows[key] = np.array([float(x) for x in vals])
+    q = bits(rows["q"].reshape(1, 1, 2))
+    k = bits(rows["k"].reshape(1, 1, 3, 2))
+    v = bits(rows["v"].reshape(1, 1, 3, 2))
+    res = decode_attn(q, k, v, np.array([3]), math.log(2.0), want_weights=True)
+    np.testing.assert_allclose(res.weights[0, 0], rows["weights"], rtol=0, atol=1e-15)
+    np.testing.assert_allclose(res.out[0, 0], rows["out"], rtol=0, atol=1e-15)
+    np.testing.assert_allclose(res.lse[0, 0], rows["lse"][0], rtol=0, atol=1e-15)
+
+
+def test_single_key_returns_its_value_row():
+    rng = np.random.default_rng(5)
+    w = make_contiguous("one", 5, 3, 4, 2, [1, 1, 1], head_dim=8)
+    res = decode_attn(w.q, w.k, w.v, w.kv_lens, w.scale, want_weights=True)
+    vf = bf16_bits_to_f32(w.v).astype(np.float64)
+    for h in range(4):
+        np.testing.assert_array_equal(res.out[:, h, :], vf[:, h // 2, 0, :])
+    np.testing.assert_array_equal(res.weights[..., 0], 1.0)
+    # LSE of a single key is its scaled score
+    qf, kf = bf16_bits_to_f32(w.q).astype(np.float64), bf16_bits_to_f32(w.k).astype(np.float64)
+    for b in range(3):
+        for h in range(4):
+            s = w.scale * math.fsum(qf[b, h] * kf[b, h // 2, 0])
+            assert abs(res.lse[b, h] - s) < 1e-14
+    del rng
+
+
+def test_scale_zero_gives_mean_of_values():
+    w = make_contiguous("mean", 6, 2, 6, 3, [9, 4], head_dim=16)
+    res = decode_attn(w.q, w.k, w.v, w.kv_lens, 0.0, want_weights=True)
+    vf = bf16_bits_to_f32(w.v).astype(np.float64)
+    for b, L in enumerate([9, 4]):
+        for h in range(6):
+            np.testing.assert_allclose(res.out[b, h], vf[b, h // 2, :L].mean(axis=0), atol=1e-15)
+            np.testing.assert_allclose(res.weights[b, h, :L], 1.0 / L, atol=1e-16)
+            assert abs(res.lse[b, h] - math.log(L)) < 1e-15
+
+
+def test_two_keys_log3_gives_quarter_and_three_quarters():
+    q, k = bits([[[1.0]]]), bits([[[[0.0], [1.0]]]])
+    v = bits([[[[8.0], [-8.0]]]])
+    res = decode_attn(q, k, v, np.array([2]), math.log(3.0), want_weights=True)
+    np.testing.assert_allclose(res.weights[0, 0], [0.25, 0.75], atol=1e-16)
+    assert abs(res.out[0, 0, 0] - (-4.0)) < 1e-15
+    assert abs(res.lse[0, 0] - math.log(4.0)) < 1e-15
+
+
+def test_sign_of_scores():
+    """A key aligned with q must outweigh a key opposed to it (a flipped sign
+    in the exponent or in the dot product reverses this)."""
+    q = bits([[[2.0, 0.0]]])
+    k = bits([[[[1.0, 0.0], [-1.0, 0.0]]]])
+    v = bits([[[[1.0, 0.0], [0.0, 1.0]]]])
+    res = decode_attn(q, k, v, np.array([2]), 1.0)
+    e = math.exp(4.0)
+    np.testing.assert_allclose(res.out[0, 0], [e / (1 + e), 1 / (1 + e)], atol=1e-15)
+
+
+def test_empty_sequence_is_zero_row_and_minus_inf():
+    w = make_contiguous("empty", 7, 3, 4, 2, [0, 3, 0], head_dim=8, cache_len=4)
+    res = decode_attn(w.q, w.k, w.v, w.kv_lens, w.scale)
+    assert np.all(res.out[[0, 2]] == 0.0) and np.all(np.isneginf(res.lse[[0, 2]]))
+    assert np.all(np.isfinite(res.out[1])) and np.all(np.isfinite(res.lse[1]))
+
+
+# --------------------------------------------------------------------------- invariants
+
+def _case(seed=21, B=3, Hq=10, Hkv=2, D=16, lens=(37, 1, 64), **kw):
+    return make_contiguous("inv", seed, B, Hq, Hkv, list(lens), head_dim=D, **kw)
+
+
+def test_weights_sum_to_one_and_are_positive():
+    w = _case()
+    res = decode_attn(w.q, w.k, w.v, w.kv_lens, w.scale, want_weights=True)
+    for b, L in enumerate(w.kv_lens):
+        assert np.all(res.weights[b, :, :L] > 0.0)
+        np.testing.assert_allclose(res.weights[b, :, :L].sum(axis=-1), 1.0, atol=1e-14)
+        assert np.all(res.weights[b, :, L:] == 0.0)
+
+
+def test_identical_keys_give_mean_of_values():
+    w = _case()
+    k = w.k.copy()
+    k[:, :, :, :] = k[:, :, :1, :]
+    res = decode_attn(w.q, k, w.v, w.kv_lens, w.scale)
+    vf = bf16_bits_to_f32(w.v).astype(np.float64)
+    for b, L in enumerate(w.kv_lens):
+        for h in range(w.num_q_heads):
+            np.testing.assert_allclose(res.out[b, h], vf[b, h // 5, :L].mean(axis=0), atol=1e-14)
+
+
+def test_single_dominant_key_returns_its_value_row():
+    w = _case(scale=1.0)
+    D = w.head_dim
+    q = bits(np.full((3, 10, D), 2.0))
+    k = bits(np.zeros((3, 2, 64, D)))
+    hot = [17, 0, 63]
+    for b, j in enumerate(hot):
+        k[b, :, j, :] = bits(np.full(D, 2.0))          # score 4*D = 64 above all others (0)
+    res = decode_attn(q, k, w.v, w.kv_lens, 1.0)
+    vf = bf16_bits_to_f32(w.v).astype(np.float64)
+    for b, j in enumerate(hot):
+        for h in range(10):
+            np.testing.assert_allclose(res.out[b, h], vf[b, h // 5, j], rtol=0, atol=1e-15 * 64)
+
+
+def test_permuting_kv_order_changes_nothing():
+    w = _case()
+    rng = np.random.default_rng(3)
+    k, v = w.k.copy(), w.v.copy()
+    for b, L in enumerate(w.kv_lens):
+        p = rng.permutation(L)
+        k[b, :, :L] = w.k[b][:, p]
+        v[b, :, :L] = w.v[b][:, p]
+    a = decode_attn(w.q, w.k, w.v, w.kv_lens, w.scale)
+    c = decode_attn(w.q, k, v, w.kv_lens, w.scale)
+    np.testing.assert_allclose(a.out, c.out, rtol=0, atol=1e-14)
+    np.testing.assert_allclose(a.lse, c.lse, rtol=0, atol=1e-14)
+
+
+def test_gqa_equals_mha_with_repeated_kv_heads():
+    w = _case()
+    G = w.num_q_heads // w.num_kv_heads
+    a = decode_attn(w.q, w.k, w.v, w.kv_lens, w.scale)
+    c = decode_attn(w.q, np.repeat(w.k, G, axis=1), np.repeat(w.v, G, axis=1), w.kv_lens, w.scale)
+    np.testing.assert_array_equal(a.out, c.out)
+    # the interleaved map h % Hkv would give something else:
+    kk = np.tile(w.k, (1, G, 1, 1))
+    d = decode_attn(w.q, kk, np.tile(w.v, (1, G, 1, 1)), w.kv_lens, w.scale)
+    assert np.abs(a.out - d.out).max() > 1e-3
+
+
+def test_identical_queries_in_a_group_give_identical_rows():
+    w = _case()
+    q = w.q.copy()
+    q[:, 0:5] = q[:, 0:1]
+    res = decode_attn(q, w.k, w.v, w.kv_lens, w.scale)
+    for h in range(1, 5):
+        np.testing.assert_array_equal(res.out[:, h], res.out[:, 0])
+    assert np.abs(res.out[:, 5] - res.out[:, 0]).max() > 1e-3      # other group: other keys
+
+
+def test_output_lies_in_convex_hull_of_values():
+    w = _case()
+    res = decode_attn(w.q, w.k, w.v, w.kv_lens, w.scale)
+    vf = bf16_bits_to_f32(w.v).astype(np.float64)
+    for b, L in enumerate(w.kv_lens):
+        for h in range(w.num_q_heads):
+            lo, hi = vf[b, h // 5, :L].min(axis=0), vf[b, h // 5, :L].max(axis=0)
+            assert np.all(res.out[b, h] >= lo - 1e-14) and np.all(res.out[b, h] <= hi + 1e-14)
+
+
+def test_padding_is_never_read():
+    w = _case(cache_len=80)
+    a = decode_attn(w.q, w.k, w.v, w.kv_lens, w.scale)
+    assert np.all(np.isfinite(a.out)) and np.all(np.isfinite(a.lse))
+    k2 = w.k.copy()
+    for b, L in enumerate(w.kv_lens):
+        k2[b, :, L:] = 0
+    c = decode_attn(w.q, k2, w.v, w.kv_lens, w.scale)
+    np.testing.assert_array_equal(a.out, c.out)
+
+
+def test_paged_equals_contiguous_for_any_block_order():
+    lens = [37, 16, 1, 50]
+    c = make_contiguous("c", 31, 4, 8, 2, lens, head_dim=16)
+    ref = decode_attn(c.q, c.k, c.v, c.kv_lens, c.scale)
+    for permute in (False, True):
+        for layout in ("head_major", "token_major"):
+            p = make_paged("p", 31, 4, 8, 2, lens, head_dim=16, permute=permute, layout=layout)
+            got = decode_attn(p.q, p.k, p.v, p.kv_lens, p.scale, block_table=p.block_table,
+                              page_size=p.page_size)
+            np.testing.assert_array_equal(ref.out, got.out)
+            np.testing.assert_array_equal(ref.lse, got.lse)
+
+
+def test_split_and_lse_merge_reproduces_one_shot():
+    """Attention over [0, L) equals the log-sum-exp weighted merge of attention
+    over [0, c) and [c, L): pins LSE (base e, of the scaled scores)."""
+    w = _case(lens=(64, 33, 50))
+    full = decode_attn(w.q, w.k, w.v, w.kv_lens, w.scale)
+    for cut in (1, 16, 31):
+        a = decode_attn(w.q, w.k[:, :, :cut], w.v[:, :, :cut], np.full(3, cut), w.scale)
+        rest = w.kv_lens - cut
+        c = decode_attn(w.q, w.k[:, :, cut:], w.v[:, :, cut:], rest, w.scale)
+        big = np.maximum(a.lse, c.lse)
+        wa, wc = np.exp(a.lse - big), np.exp(c.lse - big)
+        merged = (wa[..., None] * a.out + wc[..., None] * c.out) / (wa + wc)[..., None]
+        np.testing.assert_allclose(merged, full.out, rtol=0, atol=1e-14)
+        np.testing.assert_allclose(big + np.log(wa + wc), full.lse, rtol=0, atol=1e-14)
+
+
+def test_shift_of_all_scores_moves_lse_only():
+    """Adding a constant c to every score (one extra q/k coordinate) leaves the
+    output unchanged and moves LSE by exactly c."""
+    w = _case(D=16, scale=0.5)
+    q, k = w.q.copy(), w.k.copy()
+    q[:, :, 0] = bits(np.float32(4.0))
+    k[:, :, :, 0] = bits(np.float32(0.0))
+    a = decode_attn(q, k, w.v, w.kv_lens, 0.5)
+    k[:, :, :, 0] = bits(np.float32(1.5))            # every score grows by 0.5 * 4 * 1.5 = 3
+    c = decode_attn(q, k, w.v, w.kv_lens, 0.5)
+    np.testing.assert_allclose(a.out, c.out, rtol=0, atol=1e-13)
+    np.testing.assert_allclose(c.lse - a.lse, 3.0, rtol=0, atol=1e-13)
+
+
+# --------------------------------------------------------------------------- library third opinion
+
+@pytest.mark.parametrize("layout", ["head_major", "token_major"])
+def test_matches_float64_library_softmax(layout):
+    torch = pytest.importorskip("torch")
+    w = make_contiguous("lib", 41, 2, 10, 2, [300, 129], head_dim=128, layout=layout)
+    res = decode_attn(w.q, w.k, w.v, w.kv_lens, w.scale)
+    qf = torch.from_numpy(bf16_bits_to_f32(w.q).astype(np.float64))
+    kf = torch.from_numpy(bf16_bits_to_f32(np.ascontiguousarray(w.k)).astype(np.float64))
+    vf = torch.from_numpy(bf16_bits_to_f32(np.ascontiguousarray(w.v)).astype(np.float64))
+    for b, L in enumerate(w.kv_lens):
+        kk = kf[b, :, :L].repeat_interleave(5, dim=0)           # [Hq, L, D]
+        vv = vf[b, :, :L].repeat_interleave(5, dim=0)
+        s = torch.einsum("hd,hjd->hj", qf[b], kk) * w.scale
+        o = torch.einsum("hj,hjd->hd", torch.softmax(s, dim=-1), vv)
+        np.testing.assert_allclose(res.out[b], o.numpy(), rtol=0, atol=1e-13)
+        np.testing.assert_allclose(res.lse[b], torch.logsumexp(s, dim=-1).numpy(), rtol=0, atol=1e-12)
+
+
+def test_thread_count_does_not_change_the_result():
+    w = _case()
+    a = decode_attn(w.q, w.k, w.v, w.kv_lens, w.scale, threads=1)
+    c = decode_attn(w.q, w.k, w.v, w.kv_lens, w.scale, threads=4)
+    np.testing.assert_array_equal(a.out, c.out)
+    assert a.threads == 1 and 1 <= c.threads <= 4
