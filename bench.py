@@ -1,0 +1,157 @@
+#!/usr/bin/env python3
+"""Benchmark of the GQA decode-attention hot path on one MI355X.
+
+A step is one gqa_decode_attn call (plan + split-KV partial + combine kernels)
+on the ragged long-trace batch: B=64, Hq=40, Hkv=8, D=128, KV lengths uniform
+on [1024, 16384], head-major bf16 cache, inputs resident in HBM.  Calls
+alternate between two copies of the cache so that no call finds the previous
+call's data in a cache.
+
+Prints one JSON line: metric = KV bytes streamed per second (TB/s), with the
+HBM roofline of the split-KV partial kernel (per-kernel time from HIP events
+recorded inside the timed region) and the fp64 CPU oracle timed on the host
+cores of the same machine.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published peak
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=2, help="index into the five named configurations")
+    ap.add_argument("--chunk", type=int, default=0, help="KV tokens per split (0 = library default)")
+    ap.add_argument("--variant", type=int, default=0, help="0 = matrix-core kernel, 1 = vector-ALU kernel")
+    ap.add_argument("--layout", default="head_major")
+    ap.add_argument("--no-host-lens", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copies", type=int, default=0, help="cache copies to rotate over (0 = enough for 1 GiB)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this path runs on one GPU; --gpus N with N > 1 is not supported "
+              "(sequences and KV heads would shard across GPUs with no exchange)", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2510_07356_amd import binding, workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    torch.cuda.set_device(0)
+    t_gen = time.time()
+    w = workloads.make_config(args.config, layout=args.layout)
+    t_gen = time.time() - t_gen
+    copies = args.copies if args.copies > 0 else max(2, -(-(1 << 30) // max(w.kv_bytes, 1)))
+    copies = min(copies, 64)
+    devs = [binding.to_device(w) for _ in range(copies)]
+    params = binding.make_params(devs[0]["q"], devs[0]["k"], devs[0]["v"], w.max_kv_len, w.scale,
+                                 w.page_size, devs[0]["block_table"], args.chunk, args.variant)
+    host_lens = None if args.no_host_lens else w.kv_lens
+    plan = binding.gqa_decode_plan_info(params, host_lens)
+    ws = torch.empty(binding.gqa_decode_workspace_bytes(params), dtype=torch.uint8, device="cuda:0")
+    out = torch.empty((w.batch, w.num_q_heads, w.head_dim), dtype=torch.float32, device="cuda:0")
+    lse = torch.empty((w.batch, w.num_q_heads), dtype=torch.float32, device="cuda:0")
+    calls = [binding.Call(params, d["q"], d["k"], d["v"], d["kv_lens"], d["block_table"], host_lens,
+                          out, lse, ws) for d in devs]
+    timer = binding.Timer(args.steps)
+
+    for i in range(args.warmup):
+        calls[i % copies]()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        calls[i % copies](timer)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    n_calls, (plan_ms, partial_ms, combine_ms) = timer.read()
+    assert n_calls == args.steps
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    # the same loop without the event records, for the record only
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    for i in range(args.steps):
+        calls[i % copies]()
+    torch.cuda.synchronize()
+    ms_plain = (time.perf_counter() - t2) * 1e3 / args.steps
+
+    kv_bytes = w.kv_bytes
+    value = kv_bytes / (ms_per_step * 1e-3) / 1e12
+    partial_avg_ms = partial_ms / args.steps
+    achieved = kv_bytes / (partial_avg_ms * 1e-3) / 1e9
+
+    result = {
+        "metric": "decode_attn_kv_read_throughput",
+        "value": round(value, 4),
+        "unit": "TB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16 in, fp32 accumulate",
+        "data": "synthetic",
+        "config": {
+            "workload": f"{w.name} (configs[{args.config}]): B={w.batch} Hq={w.num_q_heads} Hkv={w.num_kv_heads} "
+                        f"D={w.head_dim} kv_tokens={w.kv_tokens} {'paged' if w.page_size else 'contiguous'} "
+                        f"{w.layout} bf16 cache",
+            "kv_bytes_per_step": kv_bytes,
+            "chunk_tokens": plan.chunk_tokens,
+            "work_items": plan.work_items,
+            "kernel_variant": args.variant,
+            "cache_copies_rotated": copies,
+        },
+        "pct_of_hbm_peak": round(100.0 * value * 1e3 / HBM_PEAK_GBPS, 2),
+        "sequences_per_s": round(w.batch / (ms_per_step * 1e-3), 1),
+        "ms_per_step_without_event_records": round(ms_plain, 5),
+        "kernel_ms": {"plan": round(plan_ms / args.steps, 5), "partial": round(partial_avg_ms, 5),
+                      "combine": round(combine_ms / args.steps, 5)},
+        "roofline": {
+            "kernel": "partial_mfma_kernel" if args.variant == 0 else "partial_valu_kernel",
+            "bound": "hbm",
+            "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBPS, 4),
+            "traffic": None,
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import decode_attn
+        t3 = time.perf_counter()
+        ref = decode_attn(w.q, w.k, w.v, w.kv_lens, w.scale, block_table=w.block_table, page_size=w.page_size)
+        t_cpu = time.perf_counter() - t3
+        calls[0]()
+        torch.cuda.synchronize()
+        err = out.double().cpu().numpy() - ref.out
+        result["cpu_baseline"] = {
+            "value": round(kv_bytes / t_cpu / 1e12, 6),
+            "unit": "TB/s",
+            "cores": ref.threads,
+            "kind": "oracle",
+            "sample": f"the whole workload once ({w.batch} sequences, {w.kv_tokens} KV tokens), {t_cpu:.2f} s wall",
+        }
+        result["parity"] = {"max_abs": float(np.abs(err).max()),
+                            "rel_l2": float(np.linalg.norm(err) / np.linalg.norm(ref.out))}
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,176 @@
+/*
+ * gqa_decode.h -- C ABI of the MI355X (gfx950) grouped-query decode-attention library.
+ *
+ * One call = the attention of ONE decode step of ONE transformer layer: every
+ * sequence b of a batch contributes one new query token that attends over all
+ * kv_lens[b] cached key/value rows of that sequence (the newest token's K/V
+ * are already in the cache, so no mask is applied).
+ *
+ * Why this operator: the method of the paper spends its run time letting a 32B
+ * grouped-query reasoning model write traces of thousands of tokens, several
+ * samples per task (Section 3.3; Table 3 gives average trace lengths of
+ * 6-7 thousand tokens, Section 4.1 a maximum of 32,768).  Every generated
+ * token re-reads the whole KV cache of its sequence in every layer, which makes
+ * this HBM-bound operator the hot loop.  The paper defines no attention
+ * variant of its own; what is computed is standard softmax attention:
+ *
+ *     g        = h / (num_q_heads / num_kv_heads)          (contiguous head groups)
+ *     s_j      = scale * sum_d Q[b,h,d] * K[b,j,g,d]        j in [0, kv_lens[b])
+ *     p_j      = exp(s_j - max_j s_j) / sum_j exp(s_j - max_j s_j)
+ *     out[b,h,d] = sum_j p_j * V[b,j,g,d]
+ *     lse[b,h]   = ln sum_j exp(s_j)                        (natural log, scaled scores)
+ *
+ * Precision: Q, K, V are bf16; scores, softmax and accumulation are fp32;
+ * out and lse are fp32.  The probabilities that multiply V are rounded to
+ * bf16 when the matrix-core path is used (the normaliser is summed from the
+ * same rounded values, so the rounding cancels to first order).
+ *
+ * Pointers: every pointer is a DEVICE pointer unless its name starts with
+ * host_.  The caller owns all buffers, including the workspace; the library
+ * allocates nothing, frees nothing and never synchronises in gqa_decode_attn.
+ * Inputs are never written.  Work is enqueued on the given HIP stream and the
+ * call returns at once.  No exception or abort crosses this boundary: every
+ * failure is a negative status and, for argument errors, nothing is launched.
+ */
+#ifndef GQA_DECODE_H
+#define GQA_DECODE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum gqa_status {
+    GQA_OK = 0,
+    GQA_ERR_INVALID_ARG = -1,          /* null pointer, non-positive size, bad stride or alignment */
+    GQA_ERR_UNSUPPORTED = -2,          /* head_dim != 128, group size > 16, page size not a power of two >= 16 */
+    GQA_ERR_WORKSPACE_TOO_SMALL = -3,  /* workspace_bytes < gqa_decode_workspace_bytes(params) */
+    GQA_ERR_LAUNCH = -4                /* the HIP runtime refused a launch or an event call */
+} gqa_status;
+
+/*
+ * Shapes and strides of one call.  Strides count bf16 ELEMENTS; the head_dim
+ * elements of one row are adjacent (stride 1) and every row must start on a
+ * 16-byte boundary (base pointers 16-byte aligned, strides multiples of 8).
+ *
+ * Contiguous cache (page_size == 0): row (b, g, t) of K starts at
+ *     k + b*k_stride_b + g*k_stride_h + t*k_stride_t,
+ * which covers both the head-major [B, Hkv, T, D] and the token-major
+ * [B, T, Hkv, D] layouts.
+ * Paged cache (page_size > 0, a power of two >= 16): token t of sequence b lives
+ * in physical block  blk = block_table[b*block_table_stride + t / page_size]
+ * at slot t % page_size, i.e. at
+ *     k + blk*k_stride_b + g*k_stride_h + (t % page_size)*k_stride_t.
+ * Block-table entries beyond ceil(kv_lens[b] / page_size) are never read.
+ */
+typedef struct gqa_decode_params {
+    int32_t batch;               /* B >= 1                                                     */
+    int32_t num_q_heads;         /* Hq, a multiple of num_kv_heads; Hq / Hkv <= 16 (<= 8 for variant 1) */
+    int32_t num_kv_heads;        /* Hkv                                                        */
+    int32_t head_dim;            /* D, must be 128                                             */
+    int32_t max_kv_len;          /* host-known upper bound of kv_lens[]; sizes grid + workspace */
+    int32_t page_size;           /* 0 = contiguous cache, else tokens per block                 */
+    int32_t block_table_stride;  /* int32 entries per block-table row (paged only)              */
+    int32_t chunk_tokens;        /* KV tokens per split; 0 = library chooses; else multiple of 64 */
+    float   scale;               /* multiplies q.k before the softmax                           */
+    int32_t kernel_variant;      /* 0 = default (matrix-core path); 1 = plain vector-ALU path   */
+    int64_t q_stride_b, q_stride_h;
+    int64_t k_stride_b, k_stride_h, k_stride_t;
+    int64_t v_stride_b, v_stride_h, v_stride_t;
+} gqa_decode_params;
+
+/* Library version, major*10000 + minor*100 + patch. */
+int gqa_decode_version(void);
+
+/* Static, never-null description of a status code. */
+const char* gqa_decode_strerror(int status);
+
+/*
+ * Bytes of device workspace gqa_decode_attn needs for these parameters (a
+ * pure host function of batch, head counts, max_kv_len and chunk_tokens).
+ * Returns 0 if the parameters are invalid or unsupported.  The workspace must
+ * be 256-byte aligned; its contents before the call do not matter and are
+ * undefined after it.
+ */
+size_t gqa_decode_workspace_bytes(const gqa_decode_params* params);
+
+/*
+ * The split the library would use: *chunk_tokens = KV tokens per split,
+ * *max_work_items = upper bound of (sequence, kv head, split) work items (the
+ * launch size when host_kv_lens is NULL).  host_kv_lens may be NULL.  If it is
+ * given, *work_items receives the exact count, else the upper bound.
+ */
+int gqa_decode_plan_info(const gqa_decode_params* params, const int32_t* host_kv_lens,
+                         int32_t* chunk_tokens, int64_t* work_items, int64_t* max_work_items);
+
+/*
+ * Enqueue one decode-attention call.
+ *
+ *   q            [B, Hq, D] bf16 via q_stride_b / q_stride_h
+ *   k, v         bf16 cache or block pools, see gqa_decode_params
+ *   kv_lens      [B] int32 (device).  Values are clamped to [0, max_kv_len] on
+ *                the device, so a stale length never reads past the bound
+ *   block_table  [B, block_table_stride] int32 (device); NULL iff page_size == 0
+ *   host_kv_lens optional HOST copy of kv_lens (may be NULL).  When given, the
+ *                launch is sized to the exact number of splits instead of the
+ *                max_kv_len bound.  Results do not depend on it.
+ *   out          [B, Hq, D] fp32, dense; every row b < B is fully overwritten;
+ *                kv_lens[b] == 0 gives a zero row
+ *   lse          [B, Hq] fp32, dense, may be NULL; -inf where kv_lens[b] == 0
+ *   workspace    >= gqa_decode_workspace_bytes(params) bytes, 256-byte aligned
+ *   stream       a hipStream_t passed as void*; NULL = the default stream
+ *
+ * Calls on different streams with different workspaces are independent.
+ * Results are deterministic for fixed parameters (no atomics on the data
+ * path).  Returns GQA_OK or a negative gqa_status.
+ */
+int gqa_decode_attn(const gqa_decode_params* params,
+                    const void* q, const void* k, const void* v,
+                    const int32_t* kv_lens, const int32_t* block_table,
+                    const int32_t* host_kv_lens,
+                    float* out, float* lse,
+                    void* workspace, size_t workspace_bytes,
+                    void* stream);
+
+/*
+ * Per-kernel timing without synchronising inside the measured region.
+ *
+ * A gqa_timer owns HIP events for up to max_calls calls.  gqa_decode_attn_timed
+ * is gqa_decode_attn plus four event records on `stream` (before the plan
+ * kernel, between the kernels, after the combine kernel); it does not wait.
+ * gqa_timer_read waits for the last recorded event and returns, summed over
+ * the calls recorded since the last reset, the elapsed milliseconds of
+ * {plan, split-KV partial, combine} in host_kernel_ms[3] and the number of
+ * calls in *host_calls; it then resets the timer.  Creating, reading and
+ * destroying a timer are not for hot loops; recording is.
+ * A timer serves one stream at a time and is not thread-safe.
+ */
+typedef struct gqa_timer gqa_timer;
+
+int  gqa_timer_create(int32_t max_calls, gqa_timer** host_out);
+void gqa_timer_destroy(gqa_timer* timer);
+int  gqa_timer_read(gqa_timer* timer, int32_t* host_calls, float host_kernel_ms[3]);
+
+int gqa_decode_attn_timed(const gqa_decode_params* params,
+                          const void* q, const void* k, const void* v,
+                          const int32_t* kv_lens, const int32_t* block_table,
+                          const int32_t* host_kv_lens,
+                          float* out, float* lse,
+                          void* workspace, size_t workspace_bytes,
+                          void* stream, gqa_timer* timer);
+
+/*
+ * Streaming-read probe for the HBM roofline: reads `bytes` (a multiple of 16)
+ * from `src` with 128-bit loads, folds them into one 32-bit word per
+ * workgroup written to `sink` (at least 4*workgroups bytes).  Used by the
+ * benchmark to report the achievable read bandwidth next to the attention
+ * kernels; not part of the attention path.
+ */
+int gqa_decode_stream_read(const void* src, size_t bytes, void* sink, int32_t workgroups, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GQA_DECODE_H */

@@ -1,0 +1,292 @@
+"""Thin ctypes binding of libgqa_decode.so (same names as include/gqa_decode.h).
+
+Argument marshalling only: torch supplies device memory and the current HIP
+stream, every step of the attention path runs in the library's kernels.
+There is no fallback: if the library is missing, import fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgqa_decode.so")
+
+GQA_OK = 0
+GQA_ERR_INVALID_ARG = -1
+GQA_ERR_UNSUPPORTED = -2
+GQA_ERR_WORKSPACE_TOO_SMALL = -3
+GQA_ERR_LAUNCH = -4
+
+EXPORTS = ("gqa_decode_version", "gqa_decode_strerror", "gqa_decode_workspace_bytes",
+           "gqa_decode_plan_info", "gqa_decode_attn", "gqa_decode_attn_timed",
+           "gqa_decode_stream_read", "gqa_timer_create", "gqa_timer_destroy", "gqa_timer_read")
+
+
+class gqa_decode_params(ctypes.Structure):
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("num_q_heads", ctypes.c_int32),
+        ("num_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+        ("max_kv_len", ctypes.c_int32), ("page_size", ctypes.c_int32),
+        ("block_table_stride", ctypes.c_int32), ("chunk_tokens", ctypes.c_int32),
+        ("scale", ctypes.c_float), ("kernel_variant", ctypes.c_int32),
+        ("q_stride_b", ctypes.c_int64), ("q_stride_h", ctypes.c_int64),
+        ("k_stride_b", ctypes.c_int64), ("k_stride_h", ctypes.c_int64), ("k_stride_t", ctypes.c_int64),
+        ("v_stride_b", ctypes.c_int64), ("v_stride_h", ctypes.c_int64), ("v_stride_t", ctypes.c_int64),
+    ]
+
+
+class GqaError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__(f"gqa_decode: {gqa_decode_strerror(status)} ({status})")
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2510_07356_amd.build` "
+                          "(or __graft_entry__.build()) first; there is no fallback path")
+    lib = ctypes.CDLL(LIB_PATH)
+    P = ctypes.POINTER(gqa_decode_params)
+    vp, i32p = ctypes.c_void_p, ctypes.c_void_p
+    lib.gqa_decode_version.restype = ctypes.c_int
+    lib.gqa_decode_version.argtypes = []
+    lib.gqa_decode_strerror.restype = ctypes.c_char_p
+    lib.gqa_decode_strerror.argtypes = [ctypes.c_int]
+    lib.gqa_decode_workspace_bytes.restype = ctypes.c_size_t
+    lib.gqa_decode_workspace_bytes.argtypes = [P]
+    lib.gqa_decode_plan_info.restype = ctypes.c_int
+    lib.gqa_decode_plan_info.argtypes = [P, i32p, ctypes.POINTER(ctypes.c_int32),
+                                         ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64)]
+    attn_args = [P, vp, vp, vp, i32p, i32p, i32p, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.gqa_decode_attn.restype = ctypes.c_int
+    lib.gqa_decode_attn.argtypes = attn_args
+    lib.gqa_decode_attn_timed.restype = ctypes.c_int
+    lib.gqa_decode_attn_timed.argtypes = attn_args + [vp]
+    lib.gqa_timer_create.restype = ctypes.c_int
+    lib.gqa_timer_create.argtypes = [ctypes.c_int32, ctypes.POINTER(ctypes.c_void_p)]
+    lib.gqa_timer_destroy.restype = None
+    lib.gqa_timer_destroy.argtypes = [vp]
+    lib.gqa_timer_read.restype = ctypes.c_int
+    lib.gqa_timer_read.argtypes = [vp, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_float)]
+    lib.gqa_decode_stream_read.restype = ctypes.c_int
+    lib.gqa_decode_stream_read.argtypes = [vp, ctypes.c_size_t, vp, ctypes.c_int32, vp]
+    return lib
+
+
+_lib = _load()
+
+
+def gqa_decode_version() -> int:
+    return _lib.gqa_decode_version()
+
+
+def gqa_decode_strerror(status: int) -> str:
+    return _lib.gqa_decode_strerror(int(status)).decode()
+
+
+def gqa_decode_workspace_bytes(params: gqa_decode_params) -> int:
+    return int(_lib.gqa_decode_workspace_bytes(ctypes.byref(params)))
+
+
+@dataclass
+class PlanInfo:
+    chunk_tokens: int
+    work_items: int
+    max_work_items: int
+
+
+def _host_lens_ptr(host_kv_lens):
+    """host_kv_lens: None or a contiguous int32 CPU tensor / numpy array."""
+    if host_kv_lens is None:
+        return None, None
+    if isinstance(host_kv_lens, torch.Tensor):
+        assert host_kv_lens.device.type == "cpu" and host_kv_lens.dtype == torch.int32
+        keep = host_kv_lens.contiguous()
+        return keep.data_ptr(), keep
+    import numpy as np
+    keep = np.ascontiguousarray(host_kv_lens, dtype=np.int32)
+    return keep.ctypes.data, keep
+
+
+def gqa_decode_plan_info(params: gqa_decode_params, host_kv_lens=None) -> PlanInfo:
+    c, w, m = ctypes.c_int32(0), ctypes.c_int64(0), ctypes.c_int64(0)
+    ptr, _keep = _host_lens_ptr(host_kv_lens)
+    rc = _lib.gqa_decode_plan_info(ctypes.byref(params), ptr, ctypes.byref(c), ctypes.byref(w), ctypes.byref(m))
+    if rc != GQA_OK:
+        raise GqaError(rc)
+    return PlanInfo(c.value, w.value, m.value)
+
+
+def make_params(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, max_kv_len: int, scale: float,
+                page_size: int = 0, block_table: Optional[torch.Tensor] = None,
+                chunk_tokens: int = 0, kernel_variant: int = 0) -> gqa_decode_params:
+    """q [B, Hq, D]; k, v indexed [b | block, kv head, token | slot, d] (any strides with a dense last axis)."""
+    p = gqa_decode_params()
+    p.batch, p.num_q_heads, p.head_dim = q.shape
+    p.num_kv_heads = k.shape[1]
+    p.max_kv_len = int(max_kv_len)
+    p.page_size = int(page_size)
+    p.block_table_stride = int(block_table.stride(0)) if block_table is not None else 0
+    p.chunk_tokens = int(chunk_tokens)
+    p.scale = float(scale)
+    p.kernel_variant = int(kernel_variant)
+    p.q_stride_b, p.q_stride_h = q.stride(0), q.stride(1)
+    p.k_stride_b, p.k_stride_h, p.k_stride_t = k.stride(0), k.stride(1), k.stride(2)
+    p.v_stride_b, p.v_stride_h, p.v_stride_t = v.stride(0), v.stride(1), v.stride(2)
+    return p
+
+
+def _check_inputs(q, k, v, kv_lens, block_table, out, lse, workspace):
+    for name, t, dt in (("q", q, torch.bfloat16), ("k", k, torch.bfloat16), ("v", v, torch.bfloat16),
+                        ("kv_lens", kv_lens, torch.int32), ("out", out, torch.float32)):
+        if not t.is_cuda or t.dtype != dt:
+            raise TypeError(f"{name} must be a {dt} device tensor")
+    if q.stride(-1) != 1 or k.stride(-1) != 1 or v.stride(-1) != 1:
+        raise ValueError("the head_dim axis must be dense")
+    if not out.is_contiguous() or (lse is not None and not lse.is_contiguous()):
+        raise ValueError("out and lse must be dense")
+    if block_table is not None and (not block_table.is_cuda or block_table.dtype != torch.int32
+                                    or block_table.stride(1) != 1):
+        raise TypeError("block_table must be an int32 device tensor with dense rows")
+    if not workspace.is_cuda or workspace.dtype != torch.uint8:
+        raise TypeError("workspace must be a uint8 device tensor")
+
+
+class Timer:
+    """gqa_timer: HIP events around the three kernels of up to max_calls calls."""
+
+    def __init__(self, max_calls: int):
+        self._h = ctypes.c_void_p()
+        rc = _lib.gqa_timer_create(int(max_calls), ctypes.byref(self._h))
+        if rc != GQA_OK:
+            raise GqaError(rc)
+
+    def read(self):
+        """Wait for the recorded calls; returns (calls, (plan_ms, partial_ms, combine_ms) summed)."""
+        n, ms = ctypes.c_int32(0), (ctypes.c_float * 3)()
+        rc = _lib.gqa_timer_read(self._h, ctypes.byref(n), ms)
+        if rc != GQA_OK:
+            raise GqaError(rc)
+        return n.value, tuple(ms)
+
+    def close(self):
+        if self._h:
+            _lib.gqa_timer_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        self.close()
+
+
+class Call:
+    """Pre-marshalled argument list of one gqa_decode_attn call, so that a timed
+    loop does nothing but cross the C ABI."""
+
+    def __init__(self, params, q, k, v, kv_lens, block_table, host_kv_lens, out, lse, workspace,
+                 stream: Optional[torch.cuda.Stream] = None):
+        _check_inputs(q, k, v, kv_lens, block_table, out, lse, workspace)
+        s = stream if stream is not None else torch.cuda.current_stream(q.device)
+        hptr, self._keep = _host_lens_ptr(host_kv_lens)
+        self._tensors = (q, k, v, kv_lens, block_table, out, lse, workspace, params)
+        self.args = [ctypes.byref(params), q.data_ptr(), k.data_ptr(), v.data_ptr(), kv_lens.data_ptr(),
+                     block_table.data_ptr() if block_table is not None else None, hptr,
+                     out.data_ptr(), lse.data_ptr() if lse is not None else None,
+                     workspace.data_ptr(), workspace.numel(), s.cuda_stream]
+
+    def __call__(self, timer: Optional[Timer] = None) -> None:
+        rc = _lib.gqa_decode_attn(*self.args) if timer is None \
+            else _lib.gqa_decode_attn_timed(*self.args, timer._h)
+        if rc != GQA_OK:
+            raise GqaError(rc)
+
+
+def gqa_decode_attn(params: gqa_decode_params, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
+                    kv_lens: torch.Tensor, block_table: Optional[torch.Tensor], host_kv_lens,
+                    out: torch.Tensor, lse: Optional[torch.Tensor], workspace: torch.Tensor,
+                    stream: Optional[torch.cuda.Stream] = None, timed: bool = False):
+    """Enqueue one call on `stream` (default: torch's current stream).  With
+    timed=True uses gqa_decode_attn_timed with a one-call timer, waits, and
+    returns (plan_ms, partial_ms, combine_ms)."""
+    _check_inputs(q, k, v, kv_lens, block_table, out, lse, workspace)
+    s = stream if stream is not None else torch.cuda.current_stream(q.device)
+    hptr, _keep = _host_lens_ptr(host_kv_lens)
+    args = [ctypes.byref(params), q.data_ptr(), k.data_ptr(), v.data_ptr(), kv_lens.data_ptr(),
+            block_table.data_ptr() if block_table is not None else None, hptr,
+            out.data_ptr(), lse.data_ptr() if lse is not None else None,
+            workspace.data_ptr(), workspace.numel(), s.cuda_stream]
+    if timed:
+        t = Timer(1)
+        rc = _lib.gqa_decode_attn_timed(*args, t._h)
+        if rc != GQA_OK:
+            raise GqaError(rc)
+        ms = t.read()[1]
+        t.close()
+        return ms
+    rc = _lib.gqa_decode_attn(*args)
+    if rc != GQA_OK:
+        raise GqaError(rc)
+    return None
+
+
+def gqa_decode_stream_read(src: torch.Tensor, sink: torch.Tensor, workgroups: int,
+                           stream: Optional[torch.cuda.Stream] = None) -> None:
+    s = stream if stream is not None else torch.cuda.current_stream(src.device)
+    nbytes = src.numel() * src.element_size()
+    if sink.numel() * sink.element_size() < 4 * workgroups:
+        raise ValueError("sink too small")
+    rc = _lib.gqa_decode_stream_read(src.data_ptr(), nbytes, sink.data_ptr(), int(workgroups), s.cuda_stream)
+    if rc != GQA_OK:
+        raise GqaError(rc)
+
+
+# ---------------------------------------------------------------------------
+# Convenience used by tests, smoke and the benchmark: numpy workload -> device
+# ---------------------------------------------------------------------------
+
+def _bf16_view(bits_np) -> torch.Tensor:
+    """uint16 bit patterns (numpy, maybe a strided view) -> bf16 CPU tensor with the same strides."""
+    import numpy as np
+    base = bits_np
+    while isinstance(base.base, np.ndarray):
+        base = base.base
+    flat = torch.from_numpy(base.reshape(-1).view(np.int16)).view(torch.bfloat16)
+    offset = (bits_np.__array_interface__["data"][0] - base.__array_interface__["data"][0]) // 2
+    return torch.as_strided(flat, bits_np.shape, [s // 2 for s in bits_np.strides], offset)
+
+
+def to_device(w, device="cuda:0"):
+    """Copy a workloads.Workload to the device, keeping its memory layout.
+    Returns dict(q, k, v, kv_lens, block_table)."""
+    def put(bits):
+        t = _bf16_view(bits)
+        # move the underlying dense storage, then rebuild the same strided view
+        dense = torch.empty(t.untyped_storage().size() // 2, dtype=torch.bfloat16, device=device)
+        src = torch.as_strided(t, (dense.numel(),), (1,), 0)
+        dense.copy_(src)
+        return torch.as_strided(dense, t.shape, t.stride(), t.storage_offset())
+    bt = torch.from_numpy(w.block_table).to(device) if w.block_table is not None else None
+    return dict(q=put(w.q), k=put(w.k), v=put(w.v),
+                kv_lens=torch.from_numpy(w.kv_lens).to(device), block_table=bt)
+
+
+def run_workload(w, dev=None, chunk_tokens: int = 0, kernel_variant: int = 0, use_host_lens: bool = True,
+                 want_lse: bool = True, timed: bool = False):
+    """One library call on a workload; returns (out, lse[, kernel_ms]) as device tensors."""
+    dev = dev if dev is not None else to_device(w)
+    q, k, v = dev["q"], dev["k"], dev["v"]
+    params = make_params(q, k, v, w.max_kv_len, w.scale, w.page_size, dev["block_table"],
+                         chunk_tokens, kernel_variant)
+    nbytes = gqa_decode_workspace_bytes(params)
+    if nbytes == 0:
+        raise GqaError(GQA_ERR_UNSUPPORTED)
+    ws = torch.full((nbytes,), 0xFF, dtype=torch.uint8, device=q.device)   # NaN poison: stale partials show up
+    out = torch.full((w.batch, w.num_q_heads, w.head_dim), float("nan"), dtype=torch.float32, device=q.device)
+    lse = torch.full((w.batch, w.num_q_heads), float("nan"), dtype=torch.float32, device=q.device) if want_lse else None
+    ms = gqa_decode_attn(params, q, k, v, dev["kv_lens"], dev["block_table"],
+                         w.kv_lens if use_host_lens else None, out, lse, ws, timed=timed)
+    return (out, lse, ms) if timed else (out, lse)

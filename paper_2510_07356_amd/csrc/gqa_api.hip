@@ -1,0 +1,262 @@
+// C-ABI layer: argument validation, split planning, workspace carving, launches.
+#include "../../include/gqa_decode.h"
+#include "gqa_internal.h"
+
+#include <cmath>
+#include <new>
+
+struct gqa_timer {
+    int32_t max_calls;
+    int32_t calls;
+    hipEvent_t* events;      // 4 per call
+};
+
+namespace {
+
+using gqa::KernelArgs;
+
+constexpr int kVersion = 100;   // 0.1.0
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline bool mult8(int64_t s) { return s % 8 == 0; }
+
+struct Plan {
+    int chunk_tokens;
+    int64_t max_items;       // Hkv * B * ceil(max_kv_len / chunk)
+    size_t off_bytes, ml_bytes, o_bytes;
+    size_t total_bytes() const { return off_bytes + ml_bytes + o_bytes; }
+};
+
+int check_shape(const gqa_decode_params* p) {
+    if (p == nullptr) return GQA_ERR_INVALID_ARG;
+    if (p->batch < 1 || p->num_q_heads < 1 || p->num_kv_heads < 1 || p->max_kv_len < 0)
+        return GQA_ERR_INVALID_ARG;
+    if (p->num_q_heads % p->num_kv_heads != 0) return GQA_ERR_INVALID_ARG;
+    if (p->page_size < 0 || p->chunk_tokens < 0) return GQA_ERR_INVALID_ARG;
+    if (p->chunk_tokens % gqa::kTileTokens != 0) return GQA_ERR_INVALID_ARG;
+    if (p->kernel_variant != 0 && p->kernel_variant != 1) return GQA_ERR_INVALID_ARG;
+    if (!std::isfinite(p->scale)) return GQA_ERR_INVALID_ARG;
+    if (p->head_dim != gqa::kHeadDim) return GQA_ERR_UNSUPPORTED;
+    const int group = p->num_q_heads / p->num_kv_heads;
+    if (group > gqa::kMaxGroup) return GQA_ERR_UNSUPPORTED;
+    if (p->kernel_variant == 1 && group > 8) return GQA_ERR_UNSUPPORTED;
+    if (p->page_size != 0) {
+        if (p->page_size < 16 || (p->page_size & (p->page_size - 1)) != 0) return GQA_ERR_UNSUPPORTED;
+        if ((int64_t)p->block_table_stride * p->page_size < p->max_kv_len) return GQA_ERR_INVALID_ARG;
+    }
+    return GQA_OK;
+}
+
+// Split size.  The chip wants a few thousand workgroups; the partial results
+// cost G*(D+2)*4 bytes per work item against chunk*512 bytes read, so splits
+// are kept as long as that allows.
+int choose_chunk(const gqa_decode_params* p) {
+    if (p->chunk_tokens > 0) return p->chunk_tokens;
+    const int64_t tokens_bound = (int64_t)p->batch * p->max_kv_len * p->num_kv_heads;
+    int chunk = 512;
+    while (chunk > 128 && tokens_bound / chunk < 4096) chunk >>= 1;
+    return chunk;
+}
+
+int make_plan(const gqa_decode_params* p, Plan* plan) {
+    const int rc = check_shape(p);
+    if (rc != GQA_OK) return rc;
+    const int group = p->num_q_heads / p->num_kv_heads;
+    plan->chunk_tokens = choose_chunk(p);
+    const int64_t per_seq = ((int64_t)p->max_kv_len + plan->chunk_tokens - 1) / plan->chunk_tokens;
+    plan->max_items = (int64_t)p->num_kv_heads * p->batch * per_seq;
+    if (plan->max_items > 0x7fffffffLL / 4) return GQA_ERR_UNSUPPORTED;
+    const size_t items = (size_t)(plan->max_items > 0 ? plan->max_items : 1);
+    plan->off_bytes = align_up(sizeof(int32_t) * ((size_t)p->batch + 1), 256);
+    plan->ml_bytes = align_up(items * group * 2 * sizeof(float), 256);
+    plan->o_bytes = align_up(items * group * gqa::kHeadDim * sizeof(float), 256);
+    return GQA_OK;
+}
+
+int64_t exact_items(const gqa_decode_params* p, const Plan& plan, const int32_t* host_kv_lens) {
+    int64_t chunks = 0;
+    for (int b = 0; b < p->batch; ++b) {
+        int64_t len = host_kv_lens[b];
+        if (len < 0) len = 0;
+        if (len > p->max_kv_len) len = p->max_kv_len;
+        chunks += (len + plan.chunk_tokens - 1) / plan.chunk_tokens;
+    }
+    return chunks * p->num_kv_heads;
+}
+
+int run(const gqa_decode_params* p, const void* q, const void* k, const void* v,
+        const int32_t* kv_lens, const int32_t* block_table, const int32_t* host_kv_lens,
+        float* out, float* lse, void* workspace, size_t workspace_bytes, void* stream,
+        gqa_timer* timer) {
+    Plan plan;
+    const int rc = make_plan(p, &plan);
+    if (rc != GQA_OK) return rc;
+    if (!q || !k || !v || !kv_lens || !out || !workspace) return GQA_ERR_INVALID_ARG;
+    if ((p->page_size != 0) != (block_table != nullptr)) return GQA_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return GQA_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return GQA_ERR_INVALID_ARG;
+    if (!mult8(p->q_stride_b) || !mult8(p->q_stride_h) || !mult8(p->k_stride_b) || !mult8(p->k_stride_h) ||
+        !mult8(p->k_stride_t) || !mult8(p->v_stride_b) || !mult8(p->v_stride_h) || !mult8(p->v_stride_t))
+        return GQA_ERR_INVALID_ARG;
+    if (p->k_stride_t < gqa::kHeadDim || p->v_stride_t < gqa::kHeadDim || p->q_stride_h < gqa::kHeadDim)
+        return GQA_ERR_INVALID_ARG;
+    if (workspace_bytes < plan.total_bytes()) return GQA_ERR_WORKSPACE_TOO_SMALL;
+
+    KernelArgs a{};
+    a.q = static_cast<const uint16_t*>(q);
+    a.k = static_cast<const uint16_t*>(k);
+    a.v = static_cast<const uint16_t*>(v);
+    a.kv_lens = kv_lens;
+    a.block_table = block_table;
+    char* ws = static_cast<char*>(workspace);
+    a.chunk_offset = reinterpret_cast<int32_t*>(ws);
+    a.part_ml = reinterpret_cast<float*>(ws + plan.off_bytes);
+    a.part_o = reinterpret_cast<float*>(ws + plan.off_bytes + plan.ml_bytes);
+    a.out = out;
+    a.lse = lse;
+    a.batch = p->batch;
+    a.num_q_heads = p->num_q_heads;
+    a.num_kv_heads = p->num_kv_heads;
+    a.group = p->num_q_heads / p->num_kv_heads;
+    a.chunk_tokens = plan.chunk_tokens;
+    a.max_kv_len = p->max_kv_len;
+    a.page_size = p->page_size;
+    a.page_shift = 0;
+    while (p->page_size > 1 && (1 << a.page_shift) < p->page_size) ++a.page_shift;
+    a.block_table_stride = p->block_table_stride;
+    a.q_stride_b = p->q_stride_b; a.q_stride_h = p->q_stride_h;
+    a.k_stride_b = p->k_stride_b; a.k_stride_h = p->k_stride_h; a.k_stride_t = p->k_stride_t;
+    a.v_stride_b = p->v_stride_b; a.v_stride_h = p->v_stride_h; a.v_stride_t = p->v_stride_t;
+    a.scale_log2e = p->scale * 1.4426950408889634f;
+
+    int64_t items = plan.max_items;
+    if (host_kv_lens != nullptr) items = exact_items(p, plan, host_kv_lens);
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipEvent_t* ev = nullptr;
+    if (timer != nullptr) {
+        if (timer->calls >= timer->max_calls) return GQA_ERR_INVALID_ARG;
+        ev = timer->events + 4 * (size_t)timer->calls;
+    }
+    int status = GQA_OK;
+    if (ev && hipEventRecord(ev[0], s) != hipSuccess) status = GQA_ERR_LAUNCH;
+    if (status == GQA_OK && gqa::launch_plan(a, s) != hipSuccess) status = GQA_ERR_LAUNCH;
+    if (status == GQA_OK && ev && hipEventRecord(ev[1], s) != hipSuccess) status = GQA_ERR_LAUNCH;
+    if (status == GQA_OK && items > 0) {
+        const hipError_t e = (p->kernel_variant == 1) ? gqa::launch_partial_valu(a, items, s)
+                                                      : gqa::launch_partial_mfma(a, items, s);
+        if (e != hipSuccess) status = GQA_ERR_LAUNCH;
+    }
+    if (status == GQA_OK && ev && hipEventRecord(ev[2], s) != hipSuccess) status = GQA_ERR_LAUNCH;
+    if (status == GQA_OK && gqa::launch_combine(a, s) != hipSuccess) status = GQA_ERR_LAUNCH;
+    if (status == GQA_OK && ev && hipEventRecord(ev[3], s) != hipSuccess) status = GQA_ERR_LAUNCH;
+    if (status == GQA_OK && timer != nullptr) ++timer->calls;
+    return status;
+}
+
+}  // namespace
+
+extern "C" {
+
+int gqa_decode_version(void) { return kVersion; }
+
+const char* gqa_decode_strerror(int status) {
+    switch (status) {
+        case GQA_OK: return "ok";
+        case GQA_ERR_INVALID_ARG: return "invalid argument";
+        case GQA_ERR_UNSUPPORTED: return "unsupported shape";
+        case GQA_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case GQA_ERR_LAUNCH: return "HIP launch failed";
+        default: return "unknown status";
+    }
+}
+
+size_t gqa_decode_workspace_bytes(const gqa_decode_params* params) {
+    Plan plan;
+    if (make_plan(params, &plan) != GQA_OK) return 0;
+    return plan.total_bytes();
+}
+
+int gqa_decode_plan_info(const gqa_decode_params* params, const int32_t* host_kv_lens,
+                         int32_t* chunk_tokens, int64_t* work_items, int64_t* max_work_items) {
+    Plan plan;
+    const int rc = make_plan(params, &plan);
+    if (rc != GQA_OK) return rc;
+    if (chunk_tokens) *chunk_tokens = plan.chunk_tokens;
+    if (max_work_items) *max_work_items = plan.max_items;
+    if (work_items) *work_items = host_kv_lens ? exact_items(params, plan, host_kv_lens) : plan.max_items;
+    return GQA_OK;
+}
+
+int gqa_decode_attn(const gqa_decode_params* params, const void* q, const void* k, const void* v,
+                    const int32_t* kv_lens, const int32_t* block_table, const int32_t* host_kv_lens,
+                    float* out, float* lse, void* workspace, size_t workspace_bytes, void* stream) {
+    return run(params, q, k, v, kv_lens, block_table, host_kv_lens, out, lse, workspace,
+               workspace_bytes, stream, nullptr);
+}
+
+int gqa_decode_attn_timed(const gqa_decode_params* params, const void* q, const void* k, const void* v,
+                          const int32_t* kv_lens, const int32_t* block_table,
+                          const int32_t* host_kv_lens, float* out, float* lse, void* workspace,
+                          size_t workspace_bytes, void* stream, gqa_timer* timer) {
+    if (timer == nullptr) return GQA_ERR_INVALID_ARG;
+    return run(params, q, k, v, kv_lens, block_table, host_kv_lens, out, lse, workspace,
+               workspace_bytes, stream, timer);
+}
+
+int gqa_timer_create(int32_t max_calls, gqa_timer** host_out) {
+    if (host_out == nullptr || max_calls < 1 || max_calls > (1 << 20)) return GQA_ERR_INVALID_ARG;
+    *host_out = nullptr;
+    gqa_timer* t = new (std::nothrow) gqa_timer{max_calls, 0, nullptr};
+    if (t == nullptr) return GQA_ERR_LAUNCH;
+    t->events = new (std::nothrow) hipEvent_t[4 * (size_t)max_calls]();
+    if (t->events == nullptr) { delete t; return GQA_ERR_LAUNCH; }
+    for (size_t i = 0; i < 4 * (size_t)max_calls; ++i) {
+        if (hipEventCreate(&t->events[i]) != hipSuccess) {
+            for (size_t j = 0; j < i; ++j) (void)hipEventDestroy(t->events[j]);
+            delete[] t->events;
+            delete t;
+            return GQA_ERR_LAUNCH;
+        }
+    }
+    *host_out = t;
+    return GQA_OK;
+}
+
+void gqa_timer_destroy(gqa_timer* timer) {
+    if (timer == nullptr) return;
+    for (size_t i = 0; i < 4 * (size_t)timer->max_calls; ++i) (void)hipEventDestroy(timer->events[i]);
+    delete[] timer->events;
+    delete timer;
+}
+
+int gqa_timer_read(gqa_timer* timer, int32_t* host_calls, float host_kernel_ms[3]) {
+    if (timer == nullptr || host_kernel_ms == nullptr) return GQA_ERR_INVALID_ARG;
+    host_kernel_ms[0] = host_kernel_ms[1] = host_kernel_ms[2] = 0.f;
+    int status = GQA_OK;
+    if (timer->calls > 0 &&
+        hipEventSynchronize(timer->events[4 * (size_t)timer->calls - 1]) != hipSuccess)
+        status = GQA_ERR_LAUNCH;
+    for (int c = 0; c < timer->calls && status == GQA_OK; ++c)
+        for (int i = 0; i < 3; ++i) {
+            float ms = 0.f;
+            if (hipEventElapsedTime(&ms, timer->events[4 * (size_t)c + i],
+                                    timer->events[4 * (size_t)c + i + 1]) != hipSuccess) {
+                status = GQA_ERR_LAUNCH;
+                break;
+            }
+            host_kernel_ms[i] += ms;
+        }
+    if (host_calls) *host_calls = timer->calls;
+    timer->calls = 0;
+    return status;
+}
+
+int gqa_decode_stream_read(const void* src, size_t bytes, void* sink, int32_t workgroups, void* stream) {
+    if (!src || !sink || workgroups < 1 || bytes % 16 != 0 || !aligned16(src)) return GQA_ERR_INVALID_ARG;
+    return gqa::launch_stream_read(src, bytes, sink, workgroups, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? GQA_OK : GQA_ERR_LAUNCH;
+}
+
+}  // extern "C"

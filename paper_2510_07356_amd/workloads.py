@@ -26,6 +26,11 @@ from typing import Optional, Sequence
 
 import numpy as np
 
+try:                                    # optional accelerator for the bf16 rounding of big arrays
+    import torch as _torch
+except ImportError:                     # pragma: no cover
+    _torch = None
+
 BF16_POISON = np.uint16(0x7FC0)   # quiet NaN: any read of padding shows up in the output
 PAGE = 16
 
@@ -33,8 +38,13 @@ _STREAM_LENS, _STREAM_Q, _STREAM_K, _STREAM_V, _STREAM_OUTLIER, _STREAM_PERM = r
 
 
 def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
-    """Round-to-nearest-even fp32 -> bf16, returned as uint16 bit patterns."""
+    """Round-to-nearest-even fp32 -> bf16, returned as uint16 bit patterns
+    (finite inputs; the draws are normal variates, never NaN or inf)."""
     x = np.asarray(x, dtype=np.float32)
+    if _torch is not None and x.size >= 1 << 16:
+        # same rounding, one fused pass instead of five numpy passes (see tests/test_workloads.py)
+        t = _torch.from_numpy(np.ascontiguousarray(x)).to(_torch.bfloat16)
+        return t.view(_torch.int16).numpy().view(np.uint16).reshape(x.shape)
     u = np.ascontiguousarray(x).reshape(-1).view(np.uint32)
     r = u + (np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1)))
     return (r >> np.uint32(16)).astype(np.uint16).reshape(x.shape)
