@@ -24,8 +24,8 @@ inline bool mult8(int64_t s) { return s % 8 == 0; }
 struct Plan {
     int chunk_tokens;
     int64_t max_items;       // Hkv * B * ceil(max_kv_len / chunk)
-    size_t off_bytes, ml_bytes, o_bytes;
-    size_t total_bytes() const { return off_bytes + ml_bytes + o_bytes; }
+    size_t off_bytes, list_bytes, ml_bytes, o_bytes;
+    size_t total_bytes() const { return off_bytes + list_bytes + ml_bytes + o_bytes; }
 };
 
 int check_shape(const gqa_decode_params* p) {
@@ -69,6 +69,7 @@ int make_plan(const gqa_decode_params* p, Plan* plan) {
     if (plan->max_items > 0x7fffffffLL / 4) return GQA_ERR_UNSUPPORTED;
     const size_t items = (size_t)(plan->max_items > 0 ? plan->max_items : 1);
     plan->off_bytes = align_up(sizeof(int32_t) * ((size_t)p->batch + 1), 256);
+    plan->list_bytes = align_up((size_t)p->batch * (size_t)(per_seq > 0 ? per_seq : 1) * 16, 256);
     plan->ml_bytes = align_up(items * group * 2 * sizeof(float), 256);
     plan->o_bytes = align_up(items * group * gqa::kHeadDim * sizeof(float), 256);
     return GQA_OK;
@@ -111,8 +112,9 @@ int run(const gqa_decode_params* p, const void* q, const void* k, const void* v,
     a.block_table = block_table;
     char* ws = static_cast<char*>(workspace);
     a.chunk_offset = reinterpret_cast<int32_t*>(ws);
-    a.part_ml = reinterpret_cast<float*>(ws + plan.off_bytes);
-    a.part_o = reinterpret_cast<float*>(ws + plan.off_bytes + plan.ml_bytes);
+    a.work_list = reinterpret_cast<int4*>(ws + plan.off_bytes);
+    a.part_ml = reinterpret_cast<float*>(ws + plan.off_bytes + plan.list_bytes);
+    a.part_o = reinterpret_cast<float*>(ws + plan.off_bytes + plan.list_bytes + plan.ml_bytes);
     a.out = out;
     a.lse = lse;
     a.batch = p->batch;

@@ -4,8 +4,9 @@
 namespace gqa {
 
 // ---------------------------------------------------------------------------
-// Plan: chunk_offset[b] = sum_{b' < b} ceil(kv_lens[b'] / chunk_tokens), one
-// workgroup, any batch size (tiles of 256 sequences with a running carry).
+// Plan: chunk_offset[b] = sum_{b' < b} ceil(kv_lens[b'] / chunk_tokens) and the
+// flat list of splits (b, t_begin, t_end); one workgroup, any batch size (tiles
+// of 256 sequences with a running carry).
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void plan_kernel(KernelArgs a) {
     __shared__ int scan[256];
@@ -30,7 +31,15 @@ __global__ __launch_bounds__(256) void plan_kernel(KernelArgs a) {
         }
         const int incl = scan[tid];
         const int c = carry;
-        if (b < a.batch) a.chunk_offset[b] = c + incl - n;
+        if (b < a.batch) {
+            const int first = c + incl - n;
+            a.chunk_offset[b] = first;
+            const int len = min(max(a.kv_lens[b], 0), a.max_kv_len);
+            for (int i = 0; i < n; ++i) {
+                const int t0 = i * a.chunk_tokens;
+                a.work_list[first + i] = make_int4(b, t0, min(len, t0 + a.chunk_tokens), 0);
+            }
+        }
         __syncthreads();
         if (tid == 255) carry = c + incl;
         __syncthreads();
@@ -44,47 +53,55 @@ hipError_t launch_plan(const KernelArgs& a, hipStream_t s) {
 }
 
 // ---------------------------------------------------------------------------
-// Combine: for each (b, h) merge the partial results of the splits of (b, g(h)):
-//   M = max_c m_c,  w_c = 2^(m_c - M),  out = sum_c w_c o_c / sum_c w_c l_c,
-//   lse = ln 2 * (M + log2 sum_c w_c l_c).
-// One workgroup of 128 threads (one per output column) per (b, g).
+// Combine: for each output row (b, h) merge the partial results of the splits of
+// (b, g(h)):  M = max_c m_c,  w_c = 2^(m_c - M),
+//   out = sum_c w_c o_c / sum_c w_c l_c,   lse = ln 2 * (M + log2 sum_c w_c l_c).
+// One wavefront per row, two columns per lane; splits are merged in order with a
+// running maximum, eight at a time so that their loads are in flight together.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(128) void combine_kernel(KernelArgs a) {
-    const int b = blockIdx.x / a.num_kv_heads;
-    const int g = blockIdx.x % a.num_kv_heads;
-    const int d = threadIdx.x;
-    const int G = a.group;
+__global__ __launch_bounds__(256) void combine_kernel(KernelArgs a) {
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= a.batch * a.num_q_heads) return;
+    const int b = row / a.num_q_heads, h = row % a.num_q_heads;
+    const int G = a.group, g = h / G, hh = h % G;
     const int32_t* __restrict__ off = a.chunk_offset;
     const int first = off[b];
     const int n = off[b + 1] - first;
-    const float* __restrict__ ml = a.part_ml;
-    const float* __restrict__ po = a.part_o;
-    for (int h = 0; h < G; ++h) {
-        float M = -INFINITY;
-        for (int c = 0; c < n; ++c) {
-            const int64_t w = (int64_t)(first + c) * a.num_kv_heads + g;
-            M = fmaxf(M, ml[(w * G + h) * 2]);
+    const float2* __restrict__ ml = reinterpret_cast<const float2*>(a.part_ml);
+    const float2* __restrict__ po = reinterpret_cast<const float2*>(a.part_o);
+    constexpr int kBatch = 8;
+    float M = -INFINITY, den = 0.f;
+    float2 acc = make_float2(0.f, 0.f);
+    for (int c0 = 0; c0 < n; c0 += kBatch) {
+        float2 mlv[kBatch], ov[kBatch];
+        for (int u = 0; u < kBatch; ++u) {
+            const int c = min(c0 + u, n - 1);
+            const int64_t w = ((int64_t)(first + c) * a.num_kv_heads + g) * G + hh;
+            mlv[u] = ml[w];
+            ov[u] = po[w * (kHeadDim / 2) + lane];
         }
-        float acc = 0.f, den = 0.f;
-        if (M > -INFINITY) {
-            for (int c = 0; c < n; ++c) {
-                const int64_t w = (int64_t)(first + c) * a.num_kv_heads + g;
-                const float m = ml[(w * G + h) * 2];
-                const float l = ml[(w * G + h) * 2 + 1];
-                const float wgt = exp2f(m - M);          // m = -inf gives 0
-                den = fmaf(wgt, l, den);
-                acc = fmaf(wgt, po[(w * G + h) * kHeadDim + d], acc);
-            }
+        for (int u = 0; u < kBatch; ++u) {
+            if (c0 + u >= n) break;
+            const float m = mlv[u].x;
+            if (m == -INFINITY) continue;            // an empty split contributes nothing
+            const float Mn = fmaxf(M, m);
+            const float sa = exp2f(M - Mn), sb = exp2f(m - Mn);
+            den = den * sa + mlv[u].y * sb;
+            acc.x = acc.x * sa + ov[u].x * sb;
+            acc.y = acc.y * sa + ov[u].y * sb;
+            M = Mn;
         }
-        const int64_t row = (int64_t)b * a.num_q_heads + (int64_t)g * G + h;
-        a.out[row * kHeadDim + d] = den > 0.f ? acc / den : 0.f;
-        if (a.lse != nullptr && d == 0)
-            a.lse[row] = den > 0.f ? 0.6931471805599453f * (M + log2f(den)) : -INFINITY;
     }
+    const float inv = den > 0.f ? 1.f / den : 0.f;
+    reinterpret_cast<float2*>(a.out)[(int64_t)row * (kHeadDim / 2) + lane] = make_float2(acc.x * inv, acc.y * inv);
+    if (a.lse != nullptr && lane == 0)
+        a.lse[row] = den > 0.f ? 0.6931471805599453f * (M + log2f(den)) : -INFINITY;
 }
 
 hipError_t launch_combine(const KernelArgs& a, hipStream_t s) {
-    hipLaunchKernelGGL(combine_kernel, dim3(a.batch * a.num_kv_heads), dim3(128), 0, s, a);
+    const int rows = a.batch * a.num_q_heads;
+    hipLaunchKernelGGL(combine_kernel, dim3((rows + 3) / 4), dim3(256), 0, s, a);
     return hipGetLastError();
 }
 

@@ -19,6 +19,7 @@ struct KernelArgs {
     const int32_t* kv_lens;
     const int32_t* block_table;
     int32_t* chunk_offset;   // [batch + 1] running sum of per-sequence split counts
+    int4* work_list;         // [split f] = (b, t_begin, t_end, 0), written by the plan kernel
     float* part_ml;          // [work item][G][2]  running max (log2 domain) and normaliser
     float* part_o;           // [work item][G][D]  unnormalised weighted value sum
     float* out;
@@ -43,20 +44,12 @@ __device__ __forceinline__ WorkItem locate_work_item(const KernelArgs& a, int w)
     WorkItem it;
     it.g = w % a.num_kv_heads;
     const int f = w / a.num_kv_heads;
-    const int total = a.chunk_offset[a.batch];
-    it.valid = f < total;
+    const int32_t* __restrict__ off = a.chunk_offset;
+    it.valid = f < off[a.batch];
     it.b = 0; it.t_begin = 0; it.t_end = 0;
     if (!it.valid) return it;
-    int lo = 0, hi = a.batch;                       // invariant: chunk_offset[lo] <= f < chunk_offset[hi]
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (a.chunk_offset[mid] <= f) lo = mid; else hi = mid;
-    }
-    it.b = lo;
-    const int c = f - a.chunk_offset[lo];
-    const int len = min(a.kv_lens[lo], a.max_kv_len);
-    it.t_begin = c * a.chunk_tokens;
-    it.t_end = min(len, it.t_begin + a.chunk_tokens);
+    const int4 e = reinterpret_cast<const int4* __restrict__>(a.work_list)[f];
+    it.b = e.x; it.t_begin = e.y; it.t_end = e.z;
     return it;
 }
 

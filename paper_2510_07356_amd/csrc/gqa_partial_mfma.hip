@@ -33,6 +33,13 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+
+// K and V are streamed once: non-temporal loads keep them from displacing anything in the caches.
+__device__ __forceinline__ uint4 load_stream16(const uint16_t* p) {
+    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
 
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
     const f32x2 v = {lo, hi};
@@ -72,11 +79,11 @@ __device__ __forceinline__ void load_tile(const KernelArgs& a, int b, int g, int
     for (int hf = 0; hf < 2; ++hf) {
         const int tk = min(tile0 + 16 * hf + i, last);        // masked rows re-read the last valid row
         const uint16_t* kp = a.k + krow[hf] + (int64_t)(tk & tmask) * a.k_stride_t + 8 * kb;
-        for (int j = 0; j < 4; ++j) t.k[hf][j] = *reinterpret_cast<const uint4*>(kp + 32 * j);
+        for (int j = 0; j < 4; ++j) t.k[hf][j] = load_stream16(kp + 32 * j);
         for (int e4 = 0; e4 < 4; ++e4) {
             const int tv = min(tile0 + 16 * hf + 4 * kb + e4, last);
             const uint16_t* vp = a.v + vrow[hf] + (int64_t)(tv & tmask) * a.v_stride_t + 8 * i;
-            t.v[4 * hf + e4] = *reinterpret_cast<const uint4*>(vp);
+            t.v[4 * hf + e4] = load_stream16(vp);
         }
     }
 }
@@ -90,14 +97,6 @@ __global__ __launch_bounds__(256, 2) void partial_mfma_kernel(KernelArgs a) {
     const int i = lane & 15, kb = lane >> 4;
     const int b = it.b, g = it.g, G = a.group;
 
-    // Q^T as the B operand: head i, columns 8*(4j+kb)+e; zero beyond the group
-    uint4 qf[4];
-    for (int j = 0; j < 4; ++j) qf[j] = make_uint4(0, 0, 0, 0);
-    if (i < G) {
-        const uint16_t* qrow = a.q + (int64_t)b * a.q_stride_b + (int64_t)(g * G + i) * a.q_stride_h;
-        for (int j = 0; j < 4; ++j) qf[j] = *reinterpret_cast<const uint4*>(qrow + 8 * (4 * j + kb));
-    }
-
     f32x4 acc[8];
     for (int x = 0; x < 8; ++x) acc[x] = (f32x4){0.f, 0.f, 0.f, 0.f};
     float m = -INFINITY, l = 0.f;
@@ -106,6 +105,15 @@ __global__ __launch_bounds__(256, 2) void partial_mfma_kernel(KernelArgs a) {
     const int n_tiles = (it.t_end - it.t_begin + 31) >> 5;
     Tile cur, nxt;
     if (wave < n_tiles) load_tile<PAGED>(a, b, g, it.t_begin + 32 * wave, it.t_end, i, kb, cur);
+
+    // Q^T as the B operand: head i, columns 8*(4j+kb)+e; zero beyond the group
+    uint4 qf[4];
+    for (int j = 0; j < 4; ++j) qf[j] = make_uint4(0, 0, 0, 0);
+    if (i < G) {
+        const uint16_t* qrow = a.q + (int64_t)b * a.q_stride_b + (int64_t)(g * G + i) * a.q_stride_h;
+        for (int j = 0; j < 4; ++j) qf[j] = *reinterpret_cast<const uint4*>(qrow + 8 * (4 * j + kb));
+    }
+
     for (int tile = wave; tile < n_tiles; tile += 4) {
         const int tile0 = it.t_begin + 32 * tile;
         if (tile + 4 < n_tiles) load_tile<PAGED>(a, b, g, tile0 + 128, it.t_end, i, kb, nxt);
