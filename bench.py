@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the GQA decode-attention hot path on one MI355X.
 
-A step is one gqa_decode_attn call (plan + split-KV partial + combine kernels)
+A step is one gqa_decode_attn call (split-KV partial + combine kernels)
 on the ragged long-trace batch: B=64, Hq=40, Hkv=8, D=128, KV lengths uniform
 on [1024, 16384], head-major bf16 cache, inputs resident in HBM.  Calls
 alternate between two copies of the cache so that no call finds the previous
@@ -32,7 +32,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=2, help="index into the five named configurations")
-    ap.add_argument("--chunk", type=int, default=0, help="KV tokens per split (0 = library default)")
+    ap.add_argument("--chunk", type=int, default=0, help="KV tokens per share (0 = one share per workgroup)")
     ap.add_argument("--variant", type=int, default=0, help="0 = matrix-core kernel, 1 = vector-ALU kernel")
     ap.add_argument("--layout", default="head_major")
     ap.add_argument("--no-host-lens", action="store_true")
@@ -78,7 +78,7 @@ def main() -> int:
         calls[i % copies](timer if i % EVENT_STRIDE == 0 else None)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    n_timed, (plan_ms, partial_ms, combine_ms) = timer.read()
+    n_timed, (partial_ms, combine_ms) = timer.read()
     assert n_timed == (args.steps + EVENT_STRIDE - 1) // EVENT_STRIDE
     ms_per_step = (t1 - t0) * 1e3 / args.steps
 
@@ -113,15 +113,15 @@ def main() -> int:
                         f"D={w.head_dim} kv_tokens={w.kv_tokens} {'paged' if w.page_size else 'contiguous'} "
                         f"{w.layout} bf16 cache",
             "kv_bytes_per_step": kv_bytes,
-            "chunk_tokens": plan.chunk_tokens,
-            "work_items": plan.work_items,
+            "share_tokens": plan.share_tokens,
+            "workgroups": plan.workgroups,
             "kernel_variant": args.variant,
             "cache_copies_rotated": copies,
         },
         "pct_of_hbm_peak": round(100.0 * value * 1e3 / HBM_PEAK_GBPS, 2),
         "sequences_per_s": round(w.batch / (ms_per_step * 1e-3), 1),
         "ms_per_step_without_event_records": round(ms_plain, 5),
-        "kernel_ms": {"plan": round(plan_ms / n_timed, 5), "partial": round(partial_avg_ms, 5),
+        "kernel_ms": {"partial": round(partial_avg_ms, 5),
                       "combine": round(combine_ms / n_timed, 5), "launches_timed": n_timed},
         "roofline": {
             "kernel": "partial_mfma_kernel" if args.variant == 0 else "partial_valu_kernel",

@@ -73,7 +73,7 @@ typedef struct gqa_decode_params {
     int32_t max_kv_len;          /* host-known upper bound of kv_lens[]; sizes grid + workspace */
     int32_t page_size;           /* 0 = contiguous cache, else tokens per block                 */
     int32_t block_table_stride;  /* int32 entries per block-table row (paged only)              */
-    int32_t chunk_tokens;        /* KV tokens per split; 0 = library chooses; else multiple of 64 */
+    int32_t chunk_tokens;        /* KV tokens per share; 0 = one share per worker; else multiple of 64 */
     float   scale;               /* multiplies q.k before the softmax                           */
     int32_t kernel_variant;      /* 0 = default (matrix-core path); 1 = plain vector-ALU path   */
     int64_t q_stride_b, q_stride_h;
@@ -89,7 +89,8 @@ const char* gqa_decode_strerror(int status);
 
 /*
  * Bytes of device workspace gqa_decode_attn needs for these parameters (a
- * pure host function of batch, head counts, max_kv_len and chunk_tokens).
+ * pure host function of batch, head counts, max_kv_len and chunk_tokens; it
+ * touches no device).
  * Returns 0 if the parameters are invalid or unsupported.  The workspace must
  * be 256-byte aligned; its contents before the call do not matter and are
  * undefined after it.
@@ -97,13 +98,22 @@ const char* gqa_decode_strerror(int status);
 size_t gqa_decode_workspace_bytes(const gqa_decode_params* params);
 
 /*
- * The split the library would use: *chunk_tokens = KV tokens per split,
- * *max_work_items = upper bound of (sequence, kv head, split) work items (the
- * launch size when host_kv_lens is NULL).  host_kv_lens may be NULL.  If it is
- * given, *work_items receives the exact count, else the upper bound.
+ * How the work is split.  The library lays the (sequence, kv head) rows end to
+ * end into one stream of 32-token tiles and cuts it into equal shares; each
+ * share is processed by one persistent worker (a wavefront of the default
+ * kernel, a workgroup of variant 1) and yields one partial result per row it
+ * touches.  chunk_tokens == 0 gives one share per worker; chunk_tokens > 0
+ * fixes the share length and the workers take shares in turn.
+ *   *share_tokens   tokens per share: chunk_tokens if given; else, when
+ *                   host_kv_lens (HOST pointer, may be NULL) is given and a
+ *                   device is present, the length the device will compute; else 0
+ *   *workgroups     persistent workgroups of the partial kernel on the current
+ *                   device (0 when no device is present)
+ *   *partial_slots  partial results the workspace holds
+ * Any output pointer may be NULL.
  */
 int gqa_decode_plan_info(const gqa_decode_params* params, const int32_t* host_kv_lens,
-                         int32_t* chunk_tokens, int64_t* work_items, int64_t* max_work_items);
+                         int32_t* share_tokens, int32_t* workgroups, int64_t* partial_slots);
 
 /*
  * Enqueue one decode-attention call.
@@ -113,9 +123,9 @@ int gqa_decode_plan_info(const gqa_decode_params* params, const int32_t* host_kv
  *   kv_lens      [B] int32 (device).  Values are clamped to [0, max_kv_len] on
  *                the device, so a stale length never reads past the bound
  *   block_table  [B, block_table_stride] int32 (device); NULL iff page_size == 0
- *   host_kv_lens optional HOST copy of kv_lens (may be NULL).  When given, the
- *                launch is sized to the exact number of splits instead of the
- *                max_kv_len bound.  Results do not depend on it.
+ *   host_kv_lens optional HOST copy of kv_lens (may be NULL).  Not needed: the
+ *                launch size does not depend on the lengths.  Accepted so that
+ *                callers that have it can pass it; results never depend on it.
  *   out          [B, Hq, D] fp32, dense; every row b < B is fully overwritten;
  *                kv_lens[b] == 0 gives a zero row
  *   lse          [B, Hq] fp32, dense, may be NULL; -inf where kv_lens[b] == 0
@@ -138,12 +148,12 @@ int gqa_decode_attn(const gqa_decode_params* params,
  * Per-kernel timing without synchronising inside the measured region.
  *
  * A gqa_timer owns HIP events for up to max_calls calls.  gqa_decode_attn_timed
- * is gqa_decode_attn plus four event records on `stream` (before the plan
- * kernel, between the kernels, after the combine kernel); it does not wait.
+ * is gqa_decode_attn plus three event records on `stream` (before the split-KV
+ * partial kernel, between the kernels, after the combine kernel); it does not wait.
  * gqa_timer_read waits for the last recorded event and returns, summed over
  * the calls recorded since the last reset, the elapsed milliseconds of
- * {plan, split-KV partial, combine} in host_kernel_ms[3] and the number of
- * calls in *host_calls; it then resets the timer.  Creating, reading and
+ * {split-KV partial, combine} in host_kernel_ms[2] and the number of calls in
+ * *host_calls; it then resets the timer.  Creating, reading and
  * destroying a timer are not for hot loops; recording is.
  * A timer serves one stream at a time and is not thread-safe.
  */
@@ -151,7 +161,7 @@ typedef struct gqa_timer gqa_timer;
 
 int  gqa_timer_create(int32_t max_calls, gqa_timer** host_out);
 void gqa_timer_destroy(gqa_timer* timer);
-int  gqa_timer_read(gqa_timer* timer, int32_t* host_calls, float host_kernel_ms[3]);
+int  gqa_timer_read(gqa_timer* timer, int32_t* host_calls, float host_kernel_ms[2]);
 
 int gqa_decode_attn_timed(const gqa_decode_params* params,
                           const void* q, const void* k, const void* v,

@@ -61,7 +61,7 @@ def _load() -> ctypes.CDLL:
     lib.gqa_decode_workspace_bytes.argtypes = [P]
     lib.gqa_decode_plan_info.restype = ctypes.c_int
     lib.gqa_decode_plan_info.argtypes = [P, i32p, ctypes.POINTER(ctypes.c_int32),
-                                         ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64)]
+                                         ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int64)]
     attn_args = [P, vp, vp, vp, i32p, i32p, i32p, vp, vp, vp, ctypes.c_size_t, vp]
     lib.gqa_decode_attn.restype = ctypes.c_int
     lib.gqa_decode_attn.argtypes = attn_args
@@ -95,9 +95,9 @@ def gqa_decode_workspace_bytes(params: gqa_decode_params) -> int:
 
 @dataclass
 class PlanInfo:
-    chunk_tokens: int
-    work_items: int
-    max_work_items: int
+    share_tokens: int
+    workgroups: int
+    partial_slots: int
 
 
 def _host_lens_ptr(host_kv_lens):
@@ -114,7 +114,7 @@ def _host_lens_ptr(host_kv_lens):
 
 
 def gqa_decode_plan_info(params: gqa_decode_params, host_kv_lens=None) -> PlanInfo:
-    c, w, m = ctypes.c_int32(0), ctypes.c_int64(0), ctypes.c_int64(0)
+    c, w, m = ctypes.c_int32(0), ctypes.c_int32(0), ctypes.c_int64(0)
     ptr, _keep = _host_lens_ptr(host_kv_lens)
     rc = _lib.gqa_decode_plan_info(ctypes.byref(params), ptr, ctypes.byref(c), ctypes.byref(w), ctypes.byref(m))
     if rc != GQA_OK:
@@ -167,8 +167,8 @@ class Timer:
             raise GqaError(rc)
 
     def read(self):
-        """Wait for the recorded calls; returns (calls, (plan_ms, partial_ms, combine_ms) summed)."""
-        n, ms = ctypes.c_int32(0), (ctypes.c_float * 3)()
+        """Wait for the recorded calls; returns (calls, (partial_ms, combine_ms) summed)."""
+        n, ms = ctypes.c_int32(0), (ctypes.c_float * 2)()
         rc = _lib.gqa_timer_read(self._h, ctypes.byref(n), ms)
         if rc != GQA_OK:
             raise GqaError(rc)
@@ -211,7 +211,7 @@ def gqa_decode_attn(params: gqa_decode_params, q: torch.Tensor, k: torch.Tensor,
                     stream: Optional[torch.cuda.Stream] = None, timed: bool = False):
     """Enqueue one call on `stream` (default: torch's current stream).  With
     timed=True uses gqa_decode_attn_timed with a one-call timer, waits, and
-    returns (plan_ms, partial_ms, combine_ms)."""
+    returns (partial_ms, combine_ms)."""
     _check_inputs(q, k, v, kv_lens, block_table, out, lse, workspace)
     s = stream if stream is not None else torch.cuda.current_stream(q.device)
     hptr, _keep = _host_lens_ptr(host_kv_lens)

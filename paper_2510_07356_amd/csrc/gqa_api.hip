@@ -2,30 +2,35 @@
 #include "../../include/gqa_decode.h"
 #include "gqa_internal.h"
 
+#include <atomic>
 #include <cmath>
 #include <new>
 
 struct gqa_timer {
     int32_t max_calls;
     int32_t calls;
-    hipEvent_t* events;      // 4 per call
+    hipEvent_t* events;      // 3 per call
 };
 
 namespace {
 
 using gqa::KernelArgs;
 
-constexpr int kVersion = 100;   // 0.1.0
+constexpr int kVersion = 200;          // 0.2.0
+constexpr int kMaxWorkgroups = 1024;   // bound of the persistent launch; the workspace is sized for it
+constexpr int kMaxWorkers = kMaxWorkgroups * gqa::kMfmaWorkersPerGroup;   // shares when none is fixed
+constexpr int kMaxDevices = 64;
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline bool mult8(int64_t s) { return s % 8 == 0; }
 
 struct Plan {
-    int chunk_tokens;
-    int64_t max_items;       // Hkv * B * ceil(max_kv_len / chunk)
-    size_t off_bytes, list_bytes, ml_bytes, o_bytes;
-    size_t total_bytes() const { return off_bytes + list_bytes + ml_bytes + o_bytes; }
+    int fixed_share_tiles;   // 0: one share per workgroup
+    int64_t max_tiles;       // Hkv * B * ceil(max_kv_len / 32)
+    int64_t slots;           // partial-result slots the workspace holds
+    size_t header_bytes, prefix_bytes, ml_bytes, o_bytes;
+    size_t total_bytes() const { return header_bytes + prefix_bytes + ml_bytes + o_bytes; }
 };
 
 int check_shape(const gqa_decode_params* p) {
@@ -34,7 +39,7 @@ int check_shape(const gqa_decode_params* p) {
         return GQA_ERR_INVALID_ARG;
     if (p->num_q_heads % p->num_kv_heads != 0) return GQA_ERR_INVALID_ARG;
     if (p->page_size < 0 || p->chunk_tokens < 0) return GQA_ERR_INVALID_ARG;
-    if (p->chunk_tokens % gqa::kTileTokens != 0) return GQA_ERR_INVALID_ARG;
+    if (p->chunk_tokens % gqa::kChunkGranule != 0) return GQA_ERR_INVALID_ARG;
     if (p->kernel_variant != 0 && p->kernel_variant != 1) return GQA_ERR_INVALID_ARG;
     if (!std::isfinite(p->scale)) return GQA_ERR_INVALID_ARG;
     if (p->head_dim != gqa::kHeadDim) return GQA_ERR_UNSUPPORTED;
@@ -48,48 +53,48 @@ int check_shape(const gqa_decode_params* p) {
     return GQA_OK;
 }
 
-// Split size.  The chip wants a few thousand workgroups; the partial results
-// cost G*(D+2)*4 bytes per work item against chunk*512 bytes read, so splits
-// are kept as long as that allows.
-int choose_chunk(const gqa_decode_params* p) {
-    if (p->chunk_tokens > 0) return p->chunk_tokens;
-    const int64_t tokens_bound = (int64_t)p->batch * p->max_kv_len * p->num_kv_heads;
-    int chunk = 512;
-    while (chunk > 128 && tokens_bound / chunk < 4096) chunk >>= 1;
-    return chunk;
-}
-
 int make_plan(const gqa_decode_params* p, Plan* plan) {
     const int rc = check_shape(p);
     if (rc != GQA_OK) return rc;
     const int group = p->num_q_heads / p->num_kv_heads;
-    plan->chunk_tokens = choose_chunk(p);
-    const int64_t per_seq = ((int64_t)p->max_kv_len + plan->chunk_tokens - 1) / plan->chunk_tokens;
-    plan->max_items = (int64_t)p->num_kv_heads * p->batch * per_seq;
-    if (plan->max_items > 0x7fffffffLL / 4) return GQA_ERR_UNSUPPORTED;
-    const size_t items = (size_t)(plan->max_items > 0 ? plan->max_items : 1);
-    plan->off_bytes = align_up(sizeof(int32_t) * ((size_t)p->batch + 1), 256);
-    plan->list_bytes = align_up((size_t)p->batch * (size_t)(per_seq > 0 ? per_seq : 1) * 16, 256);
-    plan->ml_bytes = align_up(items * group * 2 * sizeof(float), 256);
-    plan->o_bytes = align_up(items * group * gqa::kHeadDim * sizeof(float), 256);
+    plan->fixed_share_tiles = p->chunk_tokens / gqa::kTileTokens;
+    plan->max_tiles = (int64_t)p->num_kv_heads * p->batch * gqa::tiles_of(p->max_kv_len);
+    if (plan->max_tiles > 0x3fffffffLL) return GQA_ERR_UNSUPPORTED;     // stream positions are int32
+    int64_t shares = kMaxWorkers;
+    if (plan->fixed_share_tiles > 0) {
+        const int64_t fixed = (plan->max_tiles + plan->fixed_share_tiles - 1) / plan->fixed_share_tiles;
+        if (fixed > shares) shares = fixed;
+    }
+    plan->slots = shares + (int64_t)p->batch * p->num_kv_heads;
+    plan->header_bytes = 256;
+    plan->prefix_bytes = align_up(sizeof(int32_t) * ((size_t)p->batch + 1), 256);
+    plan->ml_bytes = align_up((size_t)plan->slots * group * 2 * sizeof(float), 256);
+    plan->o_bytes = align_up((size_t)plan->slots * group * gqa::kHeadDim * sizeof(float), 256);
     return GQA_OK;
 }
 
-int64_t exact_items(const gqa_decode_params* p, const Plan& plan, const int32_t* host_kv_lens) {
-    int64_t chunks = 0;
-    for (int b = 0; b < p->batch; ++b) {
-        int64_t len = host_kv_lens[b];
-        if (len < 0) len = 0;
-        if (len > p->max_kv_len) len = p->max_kv_len;
-        chunks += (len + plan.chunk_tokens - 1) / plan.chunk_tokens;
-    }
-    return chunks * p->num_kv_heads;
+// Persistent launch size of the current device: CUs x resident workgroups per CU,
+// looked up once per device and kernel variant.
+int workgroups_for(int variant) {
+    static std::atomic<int> cache[kMaxDevices][2];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 0;
+    int n = cache[dev][variant].load(std::memory_order_acquire);
+    if (n > 0) return n;
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) return 0;
+    const int occ = variant == 1 ? gqa::partial_valu_occupancy() : gqa::partial_mfma_occupancy();
+    n = cus * occ;
+    if (n > kMaxWorkgroups) n = kMaxWorkgroups;
+    cache[dev][variant].store(n, std::memory_order_release);
+    return n;
 }
 
 int run(const gqa_decode_params* p, const void* q, const void* k, const void* v,
         const int32_t* kv_lens, const int32_t* block_table, const int32_t* host_kv_lens,
         float* out, float* lse, void* workspace, size_t workspace_bytes, void* stream,
         gqa_timer* timer) {
+    (void)host_kv_lens;      // the launch size does not depend on the lengths
     Plan plan;
     const int rc = make_plan(p, &plan);
     if (rc != GQA_OK) return rc;
@@ -111,18 +116,18 @@ int run(const gqa_decode_params* p, const void* q, const void* k, const void* v,
     a.kv_lens = kv_lens;
     a.block_table = block_table;
     char* ws = static_cast<char*>(workspace);
-    a.chunk_offset = reinterpret_cast<int32_t*>(ws);
-    a.work_list = reinterpret_cast<int4*>(ws + plan.off_bytes);
-    a.part_ml = reinterpret_cast<float*>(ws + plan.off_bytes + plan.list_bytes);
-    a.part_o = reinterpret_cast<float*>(ws + plan.off_bytes + plan.list_bytes + plan.ml_bytes);
+    a.header = reinterpret_cast<int32_t*>(ws);
+    a.row_prefix = reinterpret_cast<int32_t*>(ws + plan.header_bytes);
+    a.part_ml = reinterpret_cast<float*>(ws + plan.header_bytes + plan.prefix_bytes);
+    a.part_o = reinterpret_cast<float*>(ws + plan.header_bytes + plan.prefix_bytes + plan.ml_bytes);
     a.out = out;
     a.lse = lse;
     a.batch = p->batch;
     a.num_q_heads = p->num_q_heads;
     a.num_kv_heads = p->num_kv_heads;
     a.group = p->num_q_heads / p->num_kv_heads;
-    a.chunk_tokens = plan.chunk_tokens;
     a.max_kv_len = p->max_kv_len;
+    a.fixed_share_tiles = plan.fixed_share_tiles;
     a.page_size = p->page_size;
     a.page_shift = 0;
     while (p->page_size > 1 && (1 << a.page_shift) < p->page_size) ++a.page_shift;
@@ -132,27 +137,29 @@ int run(const gqa_decode_params* p, const void* q, const void* k, const void* v,
     a.v_stride_b = p->v_stride_b; a.v_stride_h = p->v_stride_h; a.v_stride_t = p->v_stride_t;
     a.scale_log2e = p->scale * 1.4426950408889634f;
 
-    int64_t items = plan.max_items;
-    if (host_kv_lens != nullptr) items = exact_items(p, plan, host_kv_lens);
+    int workgroups = workgroups_for(p->kernel_variant);
+    if (workgroups < 1) return GQA_ERR_LAUNCH;
+    // no more workgroups than the stream can feed with shares of the minimum length
+    const int per_group = p->kernel_variant == 1 ? 1 : gqa::kMfmaWorkersPerGroup;
+    const int64_t useful = (plan.max_tiles + gqa::kMinShareTiles * per_group - 1) / (gqa::kMinShareTiles * per_group);
+    if (useful < workgroups) workgroups = (int)(useful > 0 ? useful : 1);
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipEvent_t* ev = nullptr;
     if (timer != nullptr) {
         if (timer->calls >= timer->max_calls) return GQA_ERR_INVALID_ARG;
-        ev = timer->events + 4 * (size_t)timer->calls;
+        ev = timer->events + 3 * (size_t)timer->calls;
     }
     int status = GQA_OK;
     if (ev && hipEventRecord(ev[0], s) != hipSuccess) status = GQA_ERR_LAUNCH;
-    if (status == GQA_OK && gqa::launch_plan(a, s) != hipSuccess) status = GQA_ERR_LAUNCH;
-    if (status == GQA_OK && ev && hipEventRecord(ev[1], s) != hipSuccess) status = GQA_ERR_LAUNCH;
-    if (status == GQA_OK && items > 0) {
-        const hipError_t e = (p->kernel_variant == 1) ? gqa::launch_partial_valu(a, items, s)
-                                                      : gqa::launch_partial_mfma(a, items, s);
+    if (status == GQA_OK) {
+        const hipError_t e = (p->kernel_variant == 1) ? gqa::launch_partial_valu(a, workgroups, s)
+                                                      : gqa::launch_partial_mfma(a, workgroups, s);
         if (e != hipSuccess) status = GQA_ERR_LAUNCH;
     }
+    if (status == GQA_OK && ev && hipEventRecord(ev[1], s) != hipSuccess) status = GQA_ERR_LAUNCH;
+    if (status == GQA_OK && gqa::launch_combine(a, workgroups, s) != hipSuccess) status = GQA_ERR_LAUNCH;
     if (status == GQA_OK && ev && hipEventRecord(ev[2], s) != hipSuccess) status = GQA_ERR_LAUNCH;
-    if (status == GQA_OK && gqa::launch_combine(a, s) != hipSuccess) status = GQA_ERR_LAUNCH;
-    if (status == GQA_OK && ev && hipEventRecord(ev[3], s) != hipSuccess) status = GQA_ERR_LAUNCH;
     if (status == GQA_OK && timer != nullptr) ++timer->calls;
     return status;
 }
@@ -181,13 +188,29 @@ size_t gqa_decode_workspace_bytes(const gqa_decode_params* params) {
 }
 
 int gqa_decode_plan_info(const gqa_decode_params* params, const int32_t* host_kv_lens,
-                         int32_t* chunk_tokens, int64_t* work_items, int64_t* max_work_items) {
+                         int32_t* share_tokens, int32_t* workgroups, int64_t* partial_slots) {
     Plan plan;
     const int rc = make_plan(params, &plan);
     if (rc != GQA_OK) return rc;
-    if (chunk_tokens) *chunk_tokens = plan.chunk_tokens;
-    if (max_work_items) *max_work_items = plan.max_items;
-    if (work_items) *work_items = host_kv_lens ? exact_items(params, plan, host_kv_lens) : plan.max_items;
+    int wgs = workgroups_for(params->kernel_variant);      // 0 when no device is present
+    const int per_group = params->kernel_variant == 1 ? 1 : gqa::kMfmaWorkersPerGroup;
+    const int64_t useful = (plan.max_tiles + gqa::kMinShareTiles * per_group - 1) / (gqa::kMinShareTiles * per_group);
+    if (wgs > 0 && useful < wgs) wgs = (int)(useful > 0 ? useful : 1);
+    if (workgroups) *workgroups = wgs;
+    if (partial_slots) *partial_slots = plan.slots;
+    if (share_tokens) {
+        *share_tokens = plan.fixed_share_tiles * gqa::kTileTokens;
+        if (plan.fixed_share_tiles == 0 && host_kv_lens != nullptr && wgs > 0) {
+            int64_t total = 0;
+            for (int b = 0; b < params->batch; ++b) {
+                int64_t len = host_kv_lens[b];
+                if (len < 0) len = 0;
+                if (len > params->max_kv_len) len = params->max_kv_len;
+                total += (int64_t)params->num_kv_heads * gqa::tiles_of((int)len);
+            }
+            *share_tokens = gqa::share_tiles_for(total, 0, wgs * per_group) * gqa::kTileTokens;
+        }
+    }
     return GQA_OK;
 }
 
@@ -212,9 +235,9 @@ int gqa_timer_create(int32_t max_calls, gqa_timer** host_out) {
     *host_out = nullptr;
     gqa_timer* t = new (std::nothrow) gqa_timer{max_calls, 0, nullptr};
     if (t == nullptr) return GQA_ERR_LAUNCH;
-    t->events = new (std::nothrow) hipEvent_t[4 * (size_t)max_calls]();
+    t->events = new (std::nothrow) hipEvent_t[3 * (size_t)max_calls]();
     if (t->events == nullptr) { delete t; return GQA_ERR_LAUNCH; }
-    for (size_t i = 0; i < 4 * (size_t)max_calls; ++i) {
+    for (size_t i = 0; i < 3 * (size_t)max_calls; ++i) {
         if (hipEventCreate(&t->events[i]) != hipSuccess) {
             for (size_t j = 0; j < i; ++j) (void)hipEventDestroy(t->events[j]);
             delete[] t->events;
@@ -228,23 +251,23 @@ int gqa_timer_create(int32_t max_calls, gqa_timer** host_out) {
 
 void gqa_timer_destroy(gqa_timer* timer) {
     if (timer == nullptr) return;
-    for (size_t i = 0; i < 4 * (size_t)timer->max_calls; ++i) (void)hipEventDestroy(timer->events[i]);
+    for (size_t i = 0; i < 3 * (size_t)timer->max_calls; ++i) (void)hipEventDestroy(timer->events[i]);
     delete[] timer->events;
     delete timer;
 }
 
-int gqa_timer_read(gqa_timer* timer, int32_t* host_calls, float host_kernel_ms[3]) {
+int gqa_timer_read(gqa_timer* timer, int32_t* host_calls, float host_kernel_ms[2]) {
     if (timer == nullptr || host_kernel_ms == nullptr) return GQA_ERR_INVALID_ARG;
-    host_kernel_ms[0] = host_kernel_ms[1] = host_kernel_ms[2] = 0.f;
+    host_kernel_ms[0] = host_kernel_ms[1] = 0.f;
     int status = GQA_OK;
     if (timer->calls > 0 &&
-        hipEventSynchronize(timer->events[4 * (size_t)timer->calls - 1]) != hipSuccess)
+        hipEventSynchronize(timer->events[3 * (size_t)timer->calls - 1]) != hipSuccess)
         status = GQA_ERR_LAUNCH;
     for (int c = 0; c < timer->calls && status == GQA_OK; ++c)
-        for (int i = 0; i < 3; ++i) {
+        for (int i = 0; i < 2; ++i) {
             float ms = 0.f;
-            if (hipEventElapsedTime(&ms, timer->events[4 * (size_t)c + i],
-                                    timer->events[4 * (size_t)c + i + 1]) != hipSuccess) {
+            if (hipEventElapsedTime(&ms, timer->events[3 * (size_t)c + i],
+                                    timer->events[3 * (size_t)c + i + 1]) != hipSuccess) {
                 status = GQA_ERR_LAUNCH;
                 break;
             }

@@ -1,63 +1,18 @@
-// Plan, log-sum-exp combine and the streaming-read probe.
+// Log-sum-exp combine and the streaming-read probe.
 #include "gqa_internal.h"
 
 namespace gqa {
 
 // ---------------------------------------------------------------------------
-// Plan: chunk_offset[b] = sum_{b' < b} ceil(kv_lens[b'] / chunk_tokens) and the
-// flat list of splits (b, t_begin, t_end); one workgroup, any batch size (tiles
-// of 256 sequences with a running carry).
-// ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void plan_kernel(KernelArgs a) {
-    __shared__ int scan[256];
-    __shared__ int carry;
-    const int tid = threadIdx.x;
-    if (tid == 0) carry = 0;
-    __syncthreads();
-    for (int base = 0; base < a.batch; base += 256) {
-        const int b = base + tid;
-        int n = 0;
-        if (b < a.batch) {
-            const int len = min(max(a.kv_lens[b], 0), a.max_kv_len);
-            n = (len + a.chunk_tokens - 1) / a.chunk_tokens;
-        }
-        scan[tid] = n;
-        __syncthreads();
-        for (int d = 1; d < 256; d <<= 1) {          // inclusive Hillis-Steele scan
-            const int x = (tid >= d) ? scan[tid - d] : 0;
-            __syncthreads();
-            scan[tid] += x;
-            __syncthreads();
-        }
-        const int incl = scan[tid];
-        const int c = carry;
-        if (b < a.batch) {
-            const int first = c + incl - n;
-            a.chunk_offset[b] = first;
-            const int len = min(max(a.kv_lens[b], 0), a.max_kv_len);
-            for (int i = 0; i < n; ++i) {
-                const int t0 = i * a.chunk_tokens;
-                a.work_list[first + i] = make_int4(b, t0, min(len, t0 + a.chunk_tokens), 0);
-            }
-        }
-        __syncthreads();
-        if (tid == 255) carry = c + incl;
-        __syncthreads();
-    }
-    if (tid == 0) a.chunk_offset[a.batch] = carry;
-}
-
-hipError_t launch_plan(const KernelArgs& a, hipStream_t s) {
-    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(256), 0, s, a);
-    return hipGetLastError();
-}
-
-// ---------------------------------------------------------------------------
-// Combine: for each output row (b, h) merge the partial results of the splits of
-// (b, g(h)):  M = max_c m_c,  w_c = 2^(m_c - M),
+// Combine: for each output row (b, h) merge the partial results of the shares
+// that touch row (b, g(h)) of the stream split (slots s + r for s from the share
+// holding the row's first tile to the share holding its last):
+//   M = max_c m_c,  w_c = 2^(m_c - M),
 //   out = sum_c w_c o_c / sum_c w_c l_c,   lse = ln 2 * (M + log2 sum_c w_c l_c).
-// One wavefront per row, two columns per lane; splits are merged in order with a
-// running maximum, eight at a time so that their loads are in flight together.
+// One wavefront per row, two columns per lane; pieces are merged in stream order
+// with a running maximum, eight at a time so that their loads are in flight
+// together.  The stream geometry (header, row_prefix) was written by the
+// partial kernel.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void combine_kernel(KernelArgs a) {
     const int lane = threadIdx.x & 63;
@@ -65,9 +20,18 @@ __global__ __launch_bounds__(256) void combine_kernel(KernelArgs a) {
     if (row >= a.batch * a.num_q_heads) return;
     const int b = row / a.num_q_heads, h = row % a.num_q_heads;
     const int G = a.group, g = h / G, hh = h % G;
-    const int32_t* __restrict__ off = a.chunk_offset;
-    const int first = off[b];
-    const int n = off[b + 1] - first;
+    const int32_t* __restrict__ hdr = a.header;
+    const int32_t* __restrict__ pre = a.row_prefix;
+    const int share_tiles = hdr[1];
+    const int pb = pre[b];
+    const int tiles_b = (pre[b + 1] - pb) / a.num_kv_heads;
+    const int start = pb + g * tiles_b;
+    const int r = b * a.num_kv_heads + g;
+    int s_first = 0, n = 0;
+    if (tiles_b > 0) {
+        s_first = start / share_tiles;
+        n = (start + tiles_b - 1) / share_tiles - s_first + 1;
+    }
     const float2* __restrict__ ml = reinterpret_cast<const float2*>(a.part_ml);
     const float2* __restrict__ po = reinterpret_cast<const float2*>(a.part_o);
     constexpr int kBatch = 8;
@@ -77,14 +41,14 @@ __global__ __launch_bounds__(256) void combine_kernel(KernelArgs a) {
         float2 mlv[kBatch], ov[kBatch];
         for (int u = 0; u < kBatch; ++u) {
             const int c = min(c0 + u, n - 1);
-            const int64_t w = ((int64_t)(first + c) * a.num_kv_heads + g) * G + hh;
+            const int64_t w = ((int64_t)(s_first + c) + r) * G + hh;
             mlv[u] = ml[w];
             ov[u] = po[w * (kHeadDim / 2) + lane];
         }
         for (int u = 0; u < kBatch; ++u) {
             if (c0 + u >= n) break;
             const float m = mlv[u].x;
-            if (m == -INFINITY) continue;            // an empty split contributes nothing
+            if (m == -INFINITY) continue;            // an empty piece contributes nothing
             const float Mn = fmaxf(M, m);
             const float sa = exp2f(M - Mn), sb = exp2f(m - Mn);
             den = den * sa + mlv[u].y * sb;
@@ -99,7 +63,7 @@ __global__ __launch_bounds__(256) void combine_kernel(KernelArgs a) {
         a.lse[row] = den > 0.f ? 0.6931471805599453f * (M + log2f(den)) : -INFINITY;
 }
 
-hipError_t launch_combine(const KernelArgs& a, hipStream_t s) {
+hipError_t launch_combine(const KernelArgs& a, int /*workgroups*/, hipStream_t s) {
     const int rows = a.batch * a.num_q_heads;
     hipLaunchKernelGGL(combine_kernel, dim3((rows + 3) / 4), dim3(256), 0, s, a);
     return hipGetLastError();

@@ -1,7 +1,12 @@
 // Split-KV partial kernel, matrix-core variant (kernel_variant = 0, the default).
 //
-// One workgroup (4 wavefronts) per work item (b, g, split).  A wavefront walks
-// 32-token tiles (tile index wave, wave + 4, ...).  For one tile:
+// Every wavefront is an independent persistent worker: it owns one share of the
+// stream split described in gqa_internal.h (or takes shares in turn when the
+// share length is fixed), walks its 32-token tiles in order and keeps the next
+// tile -- or the first tile of the next piece -- in flight in a second register
+// buffer while the current one is computed.  No LDS, no barrier: the partial
+// result of a piece goes from the accumulators straight to the workspace.
+// For one tile:
 //
 //   S^T[tok, head] = K[tok, :] . Q[head, :]      v_mfma_f32_16x16x32_bf16, A = K, B = Q^T
 //   online softmax per head in fp32 (base-2 exponentials), P rounded to bf16
@@ -58,157 +63,234 @@ struct Tile {            // one 32-token tile in registers
     uint4 v[8];          // [contraction slot e]
 };
 
+struct Piece {           // the part of a share inside one (b, g) row; uniform over the wavefront
+    int b, g, tile0, n, len;
+};
+
 template <bool PAGED>
-__device__ __forceinline__ void load_tile(const KernelArgs& a, int b, int g, int tile0, int t_end,
-                                          int i, int kb, Tile& t) {
-    const int last = t_end - 1;
+__device__ __forceinline__ void load_tile(const KernelArgs& a, const Piece& p, int tile, int i, int kb, Tile& t) {
+    const int tok0 = kTileTokens * (p.tile0 + tile);
+    const int last = p.len - 1;
     int64_t krow[2], vrow[2];
     for (int hf = 0; hf < 2; ++hf) {
         if (PAGED) {
-            const int tu = min(tile0 + 16 * hf, last);        // wave-uniform: one page per 16-token half
+            const int tu = min(tok0 + 16 * hf, last);         // wave-uniform: one page per 16-token half
             const int64_t blk = __builtin_amdgcn_readfirstlane(
-                a.block_table[(int64_t)b * a.block_table_stride + (tu >> a.page_shift)]);
-            krow[hf] = blk * a.k_stride_b + (int64_t)g * a.k_stride_h;
-            vrow[hf] = blk * a.v_stride_b + (int64_t)g * a.v_stride_h;
+                a.block_table[(int64_t)p.b * a.block_table_stride + (tu >> a.page_shift)]);
+            krow[hf] = blk * a.k_stride_b + (int64_t)p.g * a.k_stride_h;
+            vrow[hf] = blk * a.v_stride_b + (int64_t)p.g * a.v_stride_h;
         } else {
-            krow[hf] = (int64_t)b * a.k_stride_b + (int64_t)g * a.k_stride_h;
-            vrow[hf] = (int64_t)b * a.v_stride_b + (int64_t)g * a.v_stride_h;
+            krow[hf] = (int64_t)p.b * a.k_stride_b + (int64_t)p.g * a.k_stride_h;
+            vrow[hf] = (int64_t)p.b * a.v_stride_b + (int64_t)p.g * a.v_stride_h;
         }
     }
     const int tmask = PAGED ? (a.page_size - 1) : 0x7fffffff;
     for (int hf = 0; hf < 2; ++hf) {
-        const int tk = min(tile0 + 16 * hf + i, last);        // masked rows re-read the last valid row
+        const int tk = min(tok0 + 16 * hf + i, last);         // masked rows re-read the last valid row
         const uint16_t* kp = a.k + krow[hf] + (int64_t)(tk & tmask) * a.k_stride_t + 8 * kb;
         for (int j = 0; j < 4; ++j) t.k[hf][j] = load_stream16(kp + 32 * j);
         for (int e4 = 0; e4 < 4; ++e4) {
-            const int tv = min(tile0 + 16 * hf + 4 * kb + e4, last);
+            const int tv = min(tok0 + 16 * hf + 4 * kb + e4, last);
             const uint16_t* vp = a.v + vrow[hf] + (int64_t)(tv & tmask) * a.v_stride_t + 8 * i;
             t.v[4 * hf + e4] = load_stream16(vp);
         }
     }
 }
 
-template <bool PAGED>
-__global__ __launch_bounds__(256, 2) void partial_mfma_kernel(KernelArgs a) {
-    const WorkItem it = locate_work_item(a, blockIdx.x);
-    if (!it.valid) return;
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int i = lane & 15, kb = lane >> 4;
-    const int b = it.b, g = it.g, G = a.group;
-
-    f32x4 acc[8];
-    for (int x = 0; x < 8; ++x) acc[x] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    float m = -INFINITY, l = 0.f;
-    const float c = a.scale_log2e;
-
-    const int n_tiles = (it.t_end - it.t_begin + 31) >> 5;
-    Tile cur, nxt;
-    if (wave < n_tiles) load_tile<PAGED>(a, b, g, it.t_begin + 32 * wave, it.t_end, i, kb, cur);
-
-    // Q^T as the B operand: head i, columns 8*(4j+kb)+e; zero beyond the group
-    uint4 qf[4];
+// Q^T as the B operand: head i, columns 8*(4j+kb)+e; zero beyond the group
+__device__ __forceinline__ void load_q(const KernelArgs& a, const Piece& p, int i, int kb, uint4 (&qf)[4]) {
     for (int j = 0; j < 4; ++j) qf[j] = make_uint4(0, 0, 0, 0);
-    if (i < G) {
-        const uint16_t* qrow = a.q + (int64_t)b * a.q_stride_b + (int64_t)(g * G + i) * a.q_stride_h;
+    if (i < a.group) {
+        const uint16_t* qrow = a.q + (int64_t)p.b * a.q_stride_b + (int64_t)(p.g * a.group + i) * a.q_stride_h;
         for (int j = 0; j < 4; ++j) qf[j] = *reinterpret_cast<const uint4*>(qrow + 8 * (4 * j + kb));
     }
+}
 
-    for (int tile = wave; tile < n_tiles; tile += 4) {
-        const int tile0 = it.t_begin + 32 * tile;
-        if (tile + 4 < n_tiles) load_tile<PAGED>(a, b, g, tile0 + 128, it.t_end, i, kb, nxt);
+struct SoftmaxState {
+    f32x4 acc[8];        // O^T: M-tile x, register r -> O[head i][32kb + 8r + x]
+    float m, l;          // running maximum (log2 domain) and this lane's share of the normaliser
+};
 
-        // scores: two 16-token halves, contraction over the 128 columns in 4 steps
-        f32x4 s[2];
-        for (int hf = 0; hf < 2; ++hf) {
-            s[hf] = (f32x4){0.f, 0.f, 0.f, 0.f};
-            for (int j = 0; j < 4; ++j) s[hf] = mfma16(cur.k[hf][j], qf[j], s[hf]);
-        }
-        float sv[8];
-        float tmax = -INFINITY;
-        for (int hf = 0; hf < 2; ++hf)
-            for (int r = 0; r < 4; ++r) {
-                const int t = tile0 + 16 * hf + 4 * kb + r;
-                const float x = (t < it.t_end) ? s[hf][r] * c : -INFINITY;
-                sv[4 * hf + r] = x;
-                tmax = fmaxf(tmax, x);
-            }
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-        const float mn = fmaxf(m, tmax);          // finite: every tile holds at least one valid token
-        if (__builtin_amdgcn_ballot_w64(mn > m) != 0) {
-            const float alpha = exp2f(m - mn);    // first tile: 2^(-inf) = 0
-            l *= alpha;
-            for (int x = 0; x < 8; ++x) acc[x] *= alpha;
-            m = mn;
-        }
-        uint4 pb;
-        {
-            float p[8];
-            for (int e = 0; e < 8; ++e) p[e] = exp2f(sv[e] - m);
-            pb.x = pack_bf16(p[0], p[1]); pb.y = pack_bf16(p[2], p[3]);
-            pb.z = pack_bf16(p[4], p[5]); pb.w = pack_bf16(p[6], p[7]);
-            // the normaliser sums the rounded weights, so the rounding cancels in O / l
-            l += (bf16_lo(pb.x) + bf16_hi(pb.x)) + (bf16_lo(pb.y) + bf16_hi(pb.y)) +
-                 (bf16_lo(pb.z) + bf16_hi(pb.z)) + (bf16_lo(pb.w) + bf16_hi(pb.w));
-        }
-        // V^T operands: 8x8 transpose of 16-bit elements, then one MFMA per M-tile
-        for (int x2 = 0; x2 < 4; ++x2) {
-            const uint32_t* v0 = reinterpret_cast<const uint32_t*>(&cur.v[0]);
-            uint4 even, odd;
-            uint32_t* pe = reinterpret_cast<uint32_t*>(&even);
-            uint32_t* po = reinterpret_cast<uint32_t*>(&odd);
-            for (int p2 = 0; p2 < 4; ++p2) {
-                const uint32_t lo = v0[(2 * p2) * 4 + x2];       // slot 2*p2, columns 2*x2, 2*x2+1
-                const uint32_t hi = v0[(2 * p2 + 1) * 4 + x2];   // slot 2*p2+1
-                pe[p2] = __builtin_amdgcn_perm(hi, lo, 0x05040100u);
-                po[p2] = __builtin_amdgcn_perm(hi, lo, 0x07060302u);
-            }
-            acc[2 * x2] = mfma16(even, pb, acc[2 * x2]);
-            acc[2 * x2 + 1] = mfma16(odd, pb, acc[2 * x2 + 1]);
-        }
-        cur = nxt;
+__device__ __forceinline__ void reset(SoftmaxState& st) {
+    for (int x = 0; x < 8; ++x) st.acc[x] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    st.m = -INFINITY;
+    st.l = 0.f;
+}
+
+__device__ __forceinline__ void compute_tile(const Tile& t, const uint4 (&qf)[4], SoftmaxState& st,
+                                             int tok0, int len, int kb, float c) {
+    // scores: two 16-token halves, contraction over the 128 columns in 4 steps
+    f32x4 s[2];
+    for (int hf = 0; hf < 2; ++hf) {
+        s[hf] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        for (int j = 0; j < 4; ++j) s[hf] = mfma16(t.k[hf][j], qf[j], s[hf]);
     }
+    float sv[8];
+    float tmax = -INFINITY;
+    for (int hf = 0; hf < 2; ++hf)
+        for (int r = 0; r < 4; ++r) {
+            const int tok = tok0 + 16 * hf + 4 * kb + r;
+            const float x = (tok < len) ? s[hf][r] * c : -INFINITY;
+            sv[4 * hf + r] = x;
+            tmax = fmaxf(tmax, x);
+        }
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+    const float mn = fmaxf(st.m, tmax);           // finite: every tile holds at least one valid token
+    if (__builtin_amdgcn_ballot_w64(mn > st.m) != 0) {
+        const float alpha = exp2f(st.m - mn);     // first tile: 2^(-inf) = 0
+        st.l *= alpha;
+        for (int x = 0; x < 8; ++x) st.acc[x] *= alpha;
+        st.m = mn;
+    }
+    uint4 pb;
+    {
+        float pr[8];
+        for (int e = 0; e < 8; ++e) pr[e] = exp2f(sv[e] - st.m);
+        pb.x = pack_bf16(pr[0], pr[1]); pb.y = pack_bf16(pr[2], pr[3]);
+        pb.z = pack_bf16(pr[4], pr[5]); pb.w = pack_bf16(pr[6], pr[7]);
+        // the normaliser sums the rounded weights, so the rounding cancels in O / l
+        st.l += (bf16_lo(pb.x) + bf16_hi(pb.x)) + (bf16_lo(pb.y) + bf16_hi(pb.y)) +
+                (bf16_lo(pb.z) + bf16_hi(pb.z)) + (bf16_lo(pb.w) + bf16_hi(pb.w));
+    }
+    // V^T operands: 8x8 transpose of 16-bit elements, then one MFMA per M-tile
+    const uint32_t* v0 = reinterpret_cast<const uint32_t*>(&t.v[0]);
+    for (int x2 = 0; x2 < 4; ++x2) {
+        uint4 even, odd;
+        uint32_t* pe = reinterpret_cast<uint32_t*>(&even);
+        uint32_t* po = reinterpret_cast<uint32_t*>(&odd);
+        for (int p2 = 0; p2 < 4; ++p2) {
+            const uint32_t lo = v0[(2 * p2) * 4 + x2];       // slot 2*p2, columns 2*x2, 2*x2+1
+            const uint32_t hi = v0[(2 * p2 + 1) * 4 + x2];   // slot 2*p2+1
+            pe[p2] = __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+            po[p2] = __builtin_amdgcn_perm(hi, lo, 0x07060302u);
+        }
+        st.acc[2 * x2] = mfma16(even, pb, st.acc[2 * x2]);
+        st.acc[2 * x2 + 1] = mfma16(odd, pb, st.acc[2 * x2 + 1]);
+    }
+}
 
-    // the normaliser is spread over the 4 lanes (kb) of a head
-    l += __shfl_xor(l, 16);
+// Partial result of a finished piece: accumulators and (m, l) go to slot share + row.
+__device__ __forceinline__ void emit_piece(const KernelArgs& a, const Piece& p, int share, SoftmaxState& st,
+                                           int i, int kb) {
+    float l = st.l;
+    l += __shfl_xor(l, 16);          // the normaliser is spread over the 4 lanes (kb) of a head
     l += __shfl_xor(l, 32);
-
-    __shared__ float s_o[4][kMaxGroup][kHeadDim];
-    __shared__ float s_m[4][kMaxGroup], s_l[4][kMaxGroup];
+    const int G = a.group;
     if (i < G) {
-        for (int x = 0; x < 8; ++x)
-            for (int r = 0; r < 4; ++r) s_o[wave][i][32 * kb + 8 * r + x] = acc[x][r];
-        if (kb == 0) { s_m[wave][i] = m; s_l[wave][i] = l; }
-    }
-    __syncthreads();
-    const int64_t w = blockIdx.x;
-    for (int idx = tid; idx < G * kHeadDim; idx += 256) {
-        const int h = idx / kHeadDim, d = idx % kHeadDim;
-        const float mn = fmaxf(fmaxf(s_m[0][h], s_m[1][h]), fmaxf(s_m[2][h], s_m[3][h]));
-        const float ms = (mn == -INFINITY) ? 0.f : mn;
-        float o = 0.f, den = 0.f;
-        for (int x = 0; x < 4; ++x) {
-            const float wgt = exp2f(s_m[x][h] - ms);
-            o = fmaf(wgt, s_o[x][h][d], o);
-            den = fmaf(wgt, s_l[x][h], den);
+        const int64_t slot = (int64_t)share + (int64_t)p.b * a.num_kv_heads + p.g;
+        float* dst = a.part_o + (slot * G + i) * kHeadDim + 32 * kb;
+        for (int r = 0; r < 4; ++r) {
+            float4 lo4, hi4;
+            lo4.x = st.acc[0][r]; lo4.y = st.acc[1][r]; lo4.z = st.acc[2][r]; lo4.w = st.acc[3][r];
+            hi4.x = st.acc[4][r]; hi4.y = st.acc[5][r]; hi4.z = st.acc[6][r]; hi4.w = st.acc[7][r];
+            *reinterpret_cast<float4*>(dst + 8 * r) = lo4;
+            *reinterpret_cast<float4*>(dst + 8 * r + 4) = hi4;
         }
-        a.part_o[(w * G + h) * kHeadDim + d] = o;
-        if (d == 0) {
-            a.part_ml[(w * G + h) * 2] = mn;
-            a.part_ml[(w * G + h) * 2 + 1] = den;
+        if (kb == 0) *reinterpret_cast<float2*>(a.part_ml + (slot * G + i) * 2) = make_float2(st.m, l);
+    }
+}
+
+// The piece that follows p inside a share that still has `left` tiles after p.
+__device__ __forceinline__ Piece next_piece(const KernelArgs& a, const Piece& p, int left) {
+    Piece q = p;
+    q.tile0 = 0;
+    q.g = p.g + 1;
+    if (q.g == a.num_kv_heads) {
+        q.g = 0;
+        do { ++q.b; q.len = clamped_len(a, q.b); } while (q.len == 0 && q.b + 1 < a.batch);
+    }
+    q.n = min(tiles_of(q.len), left);
+    return q;
+}
+
+template <bool PAGED>
+__global__ __launch_bounds__(kThreads, 2) void partial_mfma_kernel(KernelArgs a) {
+    const int lane = threadIdx.x & 63;
+    const int i = lane & 15, kb = lane >> 4;
+    const float c = a.scale_log2e;
+    const int worker = __builtin_amdgcn_readfirstlane(blockIdx.x * kMfmaWorkersPerGroup + (threadIdx.x >> 6));
+    const int workers = gridDim.x * kMfmaWorkersPerGroup;
+
+    const int total = __builtin_amdgcn_readfirstlane(wave_stream_total(a));
+    const int share_tiles = share_tiles_for(total, a.fixed_share_tiles, workers);
+    const int n_shares = (total + share_tiles - 1) / share_tiles;
+    if (worker == 0) {
+        if (lane == 0) { a.header[0] = total; a.header[1] = share_tiles; }
+        if (total == 0) (void)wave_stream_locate(a, 0, a.row_prefix);     // all-zero prefix for the combine
+    }
+
+    for (int share = worker; share < n_shares; share += workers) {
+        int pos = share * share_tiles;
+        const int end = min(pos + share_tiles, total);
+        const StreamPos sp = wave_stream_locate(a, pos, share == 0 ? a.row_prefix : nullptr);
+        Piece p;
+        p.b = __builtin_amdgcn_readfirstlane(sp.b);
+        p.g = __builtin_amdgcn_readfirstlane(sp.g);
+        p.tile0 = __builtin_amdgcn_readfirstlane(sp.tile);
+        p.len = clamped_len(a, p.b);
+        p.n = min(tiles_of(p.len) - p.tile0, end - pos);
+
+        Tile bufA, bufB;
+        uint4 qf[4];
+        SoftmaxState st;
+        load_tile<PAGED>(a, p, 0, i, kb, bufA);
+        load_q(a, p, i, kb, qf);
+        reset(st);
+        bool has_next = pos + p.n < end;
+        Piece q = has_next ? next_piece(a, p, end - pos - p.n) : p;
+        int t = 0;                       // tile of p held (or arriving) in the current buffer
+
+        // One step: start the load of the tile after (p, t) into `nxt`, compute (p, t) from `cur`,
+        // close the piece if that was its last tile.  Returns false when the share is finished.
+        // The load is issued unconditionally -- when nothing follows it re-reads the current
+        // tile -- so that the number of loads in flight is the same on every path and the
+        // wait before the compute covers `cur` only, never the tile just requested.
+        auto step = [&](const Tile& cur, Tile& nxt) -> bool {
+            const bool last_of_piece = t + 1 == p.n;
+            const bool cross = last_of_piece && has_next;
+            Piece ld;
+            ld.b = cross ? q.b : p.b;
+            ld.g = cross ? q.g : p.g;
+            ld.tile0 = cross ? q.tile0 : p.tile0;
+            ld.len = cross ? q.len : p.len;
+            ld.n = 0;
+            load_tile<PAGED>(a, ld, cross ? 0 : (last_of_piece ? t : t + 1), i, kb, nxt);
+            compute_tile(cur, qf, st, kTileTokens * (p.tile0 + t), p.len, kb, c);
+            if (!last_of_piece) { ++t; return true; }
+            emit_piece(a, p, share, st, i, kb);
+            if (!has_next) return false;
+            pos += p.n;
+            p = q;
+            t = 0;
+            load_q(a, p, i, kb, qf);
+            reset(st);
+            has_next = pos + p.n < end;
+            if (has_next) q = next_piece(a, p, end - pos - p.n);
+            return true;
+        };
+        while (true) {
+            if (!step(bufA, bufB)) break;
+            if (!step(bufB, bufA)) break;
         }
     }
 }
 
 }  // namespace
 
-hipError_t launch_partial_mfma(const KernelArgs& a, int64_t work_items, hipStream_t s) {
+hipError_t launch_partial_mfma(const KernelArgs& a, int workgroups, hipStream_t s) {
     if (a.page_size == 0)
-        hipLaunchKernelGGL(partial_mfma_kernel<false>, dim3((unsigned)work_items), dim3(256), 0, s, a);
+        hipLaunchKernelGGL(partial_mfma_kernel<false>, dim3(workgroups), dim3(kThreads), 0, s, a);
     else
-        hipLaunchKernelGGL(partial_mfma_kernel<true>, dim3((unsigned)work_items), dim3(256), 0, s, a);
+        hipLaunchKernelGGL(partial_mfma_kernel<true>, dim3(workgroups), dim3(kThreads), 0, s, a);
     return hipGetLastError();
+}
+
+int partial_mfma_occupancy() {
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, partial_mfma_kernel<false>, kThreads, 0) != hipSuccess || n < 1)
+        n = 1;
+    return n;
 }
 
 }  // namespace gqa
