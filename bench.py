@@ -37,6 +37,9 @@ def main() -> int:
     ap.add_argument("--layout", default="head_major")
     ap.add_argument("--no-host-lens", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", type=int, default=0, metavar="MIB",
+                    help="also run the plain copy kernel over this many MiB, three times (counter scaling in profiles)")
+    ap.add_argument("--stream-read", action="store_true", help="also time the streaming-read probe over one cache copy")
     ap.add_argument("--copies", type=int, default=0, help="cache copies to rotate over (0 = enough for 1 GiB)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -134,11 +137,38 @@ def main() -> int:
         },
     }
 
+    if args.calibration_copy > 0:
+        n = args.calibration_copy << 20
+        src = torch.full((n,), 1, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            binding.gqa_decode_stream_copy(src, dst, 4096)
+        torch.cuda.synchronize()
+        result["calibration_copy_bytes"] = n
+        del src, dst
+    if args.stream_read:
+        kflat = devs[0]["k"].untyped_storage()
+        src = torch.empty(0, dtype=torch.uint8, device="cuda:0").set_(kflat)
+        sink = torch.empty(1 << 16, dtype=torch.int32, device="cuda:0")
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        best = float("inf")
+        for _ in range(5):
+            ev0.record()
+            binding.gqa_decode_stream_read(src, sink, 8192)
+            ev1.record()
+            ev1.synchronize()
+            best = min(best, ev0.elapsed_time(ev1))
+        result["stream_read_probe_GBps"] = round(src.numel() / best / 1e6, 1)
+
     if not args.no_cpu_baseline:
         from oracle import decode_attn
-        t3 = time.perf_counter()
-        ref = decode_attn(w.q, w.k, w.v, w.kv_lens, w.scale, block_table=w.block_table, page_size=w.page_size)
-        t_cpu = time.perf_counter() - t3
+        reps, t_cpu_total = 0, 0.0
+        while t_cpu_total < 1.5 and reps < 50:        # bounded: a few seconds of wall time on all host cores
+            t3 = time.perf_counter()
+            ref = decode_attn(w.q, w.k, w.v, w.kv_lens, w.scale, block_table=w.block_table, page_size=w.page_size)
+            t_cpu_total += time.perf_counter() - t3
+            reps += 1
+        t_cpu = t_cpu_total / reps
         calls[0]()
         torch.cuda.synchronize()
         err = out.double().cpu().numpy() - ref.out
@@ -147,7 +177,8 @@ def main() -> int:
             "unit": "TB/s",
             "cores": ref.threads,
             "kind": "oracle",
-            "sample": f"the whole workload once ({w.batch} sequences, {w.kv_tokens} KV tokens), {t_cpu:.2f} s wall",
+            "sample": f"the whole workload ({w.batch} sequences, {w.kv_tokens} KV tokens), mean of {reps} runs, "
+                      f"{t_cpu:.3f} s wall each on {ref.threads} threads",
         }
         result["parity"] = {"max_abs": float(np.abs(err).max()),
                             "rel_l2": float(np.linalg.norm(err) / np.linalg.norm(ref.out))}

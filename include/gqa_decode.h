@@ -73,7 +73,7 @@ typedef struct gqa_decode_params {
     int32_t max_kv_len;          /* host-known upper bound of kv_lens[]; sizes grid + workspace */
     int32_t page_size;           /* 0 = contiguous cache, else tokens per block                 */
     int32_t block_table_stride;  /* int32 entries per block-table row (paged only)              */
-    int32_t chunk_tokens;        /* KV tokens per share; 0 = one share per worker; else multiple of 64 */
+    int32_t chunk_tokens;        /* KV tokens per share; 0 = one share per worker; else multiple of 32 */
     float   scale;               /* multiplies q.k before the softmax                           */
     int32_t kernel_variant;      /* 0 = default (matrix-core path); 1 = plain vector-ALU path   */
     int64_t q_stride_b, q_stride_h;
@@ -179,6 +179,15 @@ int gqa_decode_attn_timed(const gqa_decode_params* params,
  * kernels; not part of the attention path.
  */
 int gqa_decode_stream_read(const void* src, size_t bytes, void* sink, int32_t workgroups, void* stream);
+
+/*
+ * Plain device-to-device copy of `bytes` (a multiple of 16; src and dst
+ * 16-byte aligned, not overlapping) by a grid-stride kernel.  It reads and
+ * writes exactly `bytes` each, which makes it the known-size reference that
+ * hardware byte counters of a profile are scaled by; not part of the
+ * attention path.
+ */
+int gqa_decode_stream_copy(const void* src, void* dst, size_t bytes, int32_t workgroups, void* stream);
 
 #ifdef __cplusplus
 }

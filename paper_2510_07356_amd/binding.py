@@ -14,7 +14,8 @@ from typing import Optional
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libgqa_decode.so")
+# GQA_DECODE_LIBRARY selects another build of the same library (e.g. one compiled with other tunables)
+LIB_PATH = os.environ.get("GQA_DECODE_LIBRARY") or os.path.join(_HERE, "libgqa_decode.so")
 
 GQA_OK = 0
 GQA_ERR_INVALID_ARG = -1
@@ -24,7 +25,7 @@ GQA_ERR_LAUNCH = -4
 
 EXPORTS = ("gqa_decode_version", "gqa_decode_strerror", "gqa_decode_workspace_bytes",
            "gqa_decode_plan_info", "gqa_decode_attn", "gqa_decode_attn_timed",
-           "gqa_decode_stream_read", "gqa_timer_create", "gqa_timer_destroy", "gqa_timer_read")
+           "gqa_decode_stream_read", "gqa_decode_stream_copy", "gqa_timer_create", "gqa_timer_destroy", "gqa_timer_read")
 
 
 class gqa_decode_params(ctypes.Structure):
@@ -75,6 +76,8 @@ def _load() -> ctypes.CDLL:
     lib.gqa_timer_read.argtypes = [vp, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_float)]
     lib.gqa_decode_stream_read.restype = ctypes.c_int
     lib.gqa_decode_stream_read.argtypes = [vp, ctypes.c_size_t, vp, ctypes.c_int32, vp]
+    lib.gqa_decode_stream_copy.restype = ctypes.c_int
+    lib.gqa_decode_stream_copy.argtypes = [vp, vp, ctypes.c_size_t, ctypes.c_int32, vp]
     return lib
 
 
@@ -240,6 +243,17 @@ def gqa_decode_stream_read(src: torch.Tensor, sink: torch.Tensor, workgroups: in
     if sink.numel() * sink.element_size() < 4 * workgroups:
         raise ValueError("sink too small")
     rc = _lib.gqa_decode_stream_read(src.data_ptr(), nbytes, sink.data_ptr(), int(workgroups), s.cuda_stream)
+    if rc != GQA_OK:
+        raise GqaError(rc)
+
+
+def gqa_decode_stream_copy(src: torch.Tensor, dst: torch.Tensor, workgroups: int,
+                           stream: Optional[torch.cuda.Stream] = None) -> None:
+    s = stream if stream is not None else torch.cuda.current_stream(src.device)
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("src and dst differ in size")
+    rc = _lib.gqa_decode_stream_copy(src.data_ptr(), dst.data_ptr(), nbytes, int(workgroups), s.cuda_stream)
     if rc != GQA_OK:
         raise GqaError(rc)
 

@@ -22,9 +22,10 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
-def build_library(verbose: bool = False) -> str:
+def build_library(verbose: bool = False, out: str = LIB, defines=()) -> str:
+    """defines: extra -D tunables (see the #ifndef blocks at the top of the kernels)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, "-o", LIB, *sources()]
+    cmd = [hipcc, *HIPCC_FLAGS, *[f"-D{d}" for d in defines], "-o", out, *sources()]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -33,7 +34,7 @@ def build_library(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed")
     if verbose and res.stdout.strip():
         print(res.stdout)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":

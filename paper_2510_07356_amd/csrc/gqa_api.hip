@@ -18,7 +18,7 @@ using gqa::KernelArgs;
 
 constexpr int kVersion = 200;          // 0.2.0
 constexpr int kMaxWorkgroups = 1024;   // bound of the persistent launch; the workspace is sized for it
-constexpr int kMaxWorkers = kMaxWorkgroups * gqa::kMfmaWorkersPerGroup;   // shares when none is fixed
+constexpr int kMaxWorkers = kMaxWorkgroups * gqa::kMaxWorkersPerGroup;   // shares when none is fixed
 constexpr int kMaxDevices = 64;
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -140,7 +140,7 @@ int run(const gqa_decode_params* p, const void* q, const void* k, const void* v,
     int workgroups = workgroups_for(p->kernel_variant);
     if (workgroups < 1) return GQA_ERR_LAUNCH;
     // no more workgroups than the stream can feed with shares of the minimum length
-    const int per_group = p->kernel_variant == 1 ? 1 : gqa::kMfmaWorkersPerGroup;
+    const int per_group = p->kernel_variant == 1 ? 1 : gqa::partial_mfma_workers_per_group();
     const int64_t useful = (plan.max_tiles + gqa::kMinShareTiles * per_group - 1) / (gqa::kMinShareTiles * per_group);
     if (useful < workgroups) workgroups = (int)(useful > 0 ? useful : 1);
 
@@ -193,7 +193,7 @@ int gqa_decode_plan_info(const gqa_decode_params* params, const int32_t* host_kv
     const int rc = make_plan(params, &plan);
     if (rc != GQA_OK) return rc;
     int wgs = workgroups_for(params->kernel_variant);      // 0 when no device is present
-    const int per_group = params->kernel_variant == 1 ? 1 : gqa::kMfmaWorkersPerGroup;
+    const int per_group = params->kernel_variant == 1 ? 1 : gqa::partial_mfma_workers_per_group();
     const int64_t useful = (plan.max_tiles + gqa::kMinShareTiles * per_group - 1) / (gqa::kMinShareTiles * per_group);
     if (wgs > 0 && useful < wgs) wgs = (int)(useful > 0 ? useful : 1);
     if (workgroups) *workgroups = wgs;
@@ -281,6 +281,13 @@ int gqa_timer_read(gqa_timer* timer, int32_t* host_calls, float host_kernel_ms[2
 int gqa_decode_stream_read(const void* src, size_t bytes, void* sink, int32_t workgroups, void* stream) {
     if (!src || !sink || workgroups < 1 || bytes % 16 != 0 || !aligned16(src)) return GQA_ERR_INVALID_ARG;
     return gqa::launch_stream_read(src, bytes, sink, workgroups, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? GQA_OK : GQA_ERR_LAUNCH;
+}
+
+int gqa_decode_stream_copy(const void* src, void* dst, size_t bytes, int32_t workgroups, void* stream) {
+    if (!src || !dst || workgroups < 1 || bytes % 16 != 0 || !aligned16(src) || !aligned16(dst))
+        return GQA_ERR_INVALID_ARG;
+    return gqa::launch_stream_copy(src, dst, bytes, workgroups, static_cast<hipStream_t>(stream)) == hipSuccess
                ? GQA_OK : GQA_ERR_LAUNCH;
 }
 

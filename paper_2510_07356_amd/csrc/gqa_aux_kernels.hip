@@ -39,23 +39,30 @@ __global__ __launch_bounds__(256) void combine_kernel(KernelArgs a) {
     float2 acc = make_float2(0.f, 0.f);
     for (int c0 = 0; c0 < n; c0 += kBatch) {
         float2 mlv[kBatch], ov[kBatch];
+#pragma unroll
         for (int u = 0; u < kBatch; ++u) {
             const int c = min(c0 + u, n - 1);
             const int64_t w = ((int64_t)(s_first + c) + r) * G + hh;
             mlv[u] = ml[w];
             ov[u] = po[w * (kHeadDim / 2) + lane];
         }
+        float bm = M;
+#pragma unroll
         for (int u = 0; u < kBatch; ++u) {
-            if (c0 + u >= n) break;
-            const float m = mlv[u].x;
-            if (m == -INFINITY) continue;            // an empty piece contributes nothing
-            const float Mn = fmaxf(M, m);
-            const float sa = exp2f(M - Mn), sb = exp2f(m - Mn);
-            den = den * sa + mlv[u].y * sb;
-            acc.x = acc.x * sa + ov[u].x * sb;
-            acc.y = acc.y * sa + ov[u].y * sb;
-            M = Mn;
+            if (c0 + u >= n) mlv[u].x = -INFINITY;       // duplicates of the last piece count once
+            bm = fmaxf(bm, mlv[u].x);
         }
+        const float ms = (bm == -INFINITY) ? 0.f : bm;   // keeps (-inf) - (-inf) out
+        const float sa = exp2f(M - ms);
+        den *= sa; acc.x *= sa; acc.y *= sa;
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const float wgt = exp2f(mlv[u].x - ms);      // an empty or absent piece gets weight 0
+            den = fmaf(wgt, mlv[u].y, den);
+            acc.x = fmaf(wgt, ov[u].x, acc.x);
+            acc.y = fmaf(wgt, ov[u].y, acc.y);
+        }
+        M = bm;
     }
     const float inv = den > 0.f ? 1.f / den : 0.f;
     reinterpret_cast<float2*>(a.out)[(int64_t)row * (kHeadDim / 2) + lane] = make_float2(acc.x * inv, acc.y * inv);
@@ -70,24 +77,21 @@ hipError_t launch_combine(const KernelArgs& a, int /*workgroups*/, hipStream_t s
 }
 
 // ---------------------------------------------------------------------------
-// Streaming read probe: grid-stride 128-bit loads, xor-folded.
+// Streaming read probe: grid-stride non-temporal 128-bit loads, xor-folded.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restrict__ src, size_t n16,
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* __restrict__ src, size_t n16,
                                                           uint32_t* __restrict__ sink) {
     const size_t stride = (size_t)gridDim.x * 256 * 4;
-    uint4 acc = make_uint4(0, 0, 0, 0);
+    u32x4 acc = {0, 0, 0, 0};
     size_t i = (size_t)blockIdx.x * 256 * 4 + threadIdx.x;
-    for (; i + 3 * 256 < n16; i += stride) {             // four independent loads in flight
-        const uint4 x0 = src[i], x1 = src[i + 256], x2 = src[i + 512], x3 = src[i + 768];
-        acc.x ^= x0.x ^ x1.x ^ x2.x ^ x3.x;
-        acc.y ^= x0.y ^ x1.y ^ x2.y ^ x3.y;
-        acc.z ^= x0.z ^ x1.z ^ x2.z ^ x3.z;
-        acc.w ^= x0.w ^ x1.w ^ x2.w ^ x3.w;
+    for (; i + 3 * 256 < n16; i += stride) {             // four independent non-temporal loads in flight
+        const u32x4 x0 = __builtin_nontemporal_load(src + i), x1 = __builtin_nontemporal_load(src + i + 256);
+        const u32x4 x2 = __builtin_nontemporal_load(src + i + 512), x3 = __builtin_nontemporal_load(src + i + 768);
+        acc ^= x0 ^ x1 ^ x2 ^ x3;
     }
-    for (; i < n16; i += 256) {                          // ragged end of the last full stride
-        const uint4 x = src[i];
-        acc.x ^= x.x; acc.y ^= x.y; acc.z ^= x.z; acc.w ^= x.w;
-    }
+    for (; i < n16; i += 256) acc ^= __builtin_nontemporal_load(src + i);   // ragged end of the last full stride
     uint32_t r = acc.x ^ acc.y ^ acc.z ^ acc.w;
     for (int o = 32; o > 0; o >>= 1) r ^= __shfl_xor(r, o);
     __shared__ uint32_t red[4];
@@ -98,7 +102,23 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restric
 
 hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, int workgroups, hipStream_t s) {
     hipLaunchKernelGGL(stream_read_kernel, dim3(workgroups), dim3(256), 0, s,
-                       (const uint4*)src, bytes / 16, (uint32_t*)sink);
+                       (const u32x4*)src, bytes / 16, (uint32_t*)sink);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Plain copy of n16 16-byte words (grid-stride): the known-size kernel against
+// which the HBM byte counters of a profile are scaled.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void stream_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst,
+                                                          size_t n16) {
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+hipError_t launch_stream_copy(const void* src, void* dst, size_t bytes, int workgroups, hipStream_t s) {
+    hipLaunchKernelGGL(stream_copy_kernel, dim3(workgroups), dim3(256), 0, s,
+                       (const uint4*)src, (uint4*)dst, bytes / 16);
     return hipGetLastError();
 }
 

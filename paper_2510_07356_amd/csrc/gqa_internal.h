@@ -23,7 +23,7 @@ namespace gqa {
 constexpr int kHeadDim = 128;        // the only supported head size
 constexpr int kMaxGroup = 16;        // query heads per KV head served by one K/V read
 constexpr int kTileTokens = 32;      // one MFMA tile; the unit of the stream split
-constexpr int kChunkGranule = 64;    // chunk_tokens must be a multiple of this
+constexpr int kChunkGranule = 32;    // chunk_tokens must be a multiple of this
 constexpr int kMinShareTiles = 4;    // shares are never shorter than this (128 tokens)
 constexpr int kThreads = 256;        // workgroup size of the partial kernels
 
@@ -175,8 +175,10 @@ hipError_t launch_partial_valu(const KernelArgs& a, int workgroups, hipStream_t 
 hipError_t launch_partial_mfma(const KernelArgs& a, int workgroups, hipStream_t s);
 hipError_t launch_combine(const KernelArgs& a, int workgroups, hipStream_t s);
 hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, int workgroups, hipStream_t s);
+hipError_t launch_stream_copy(const void* src, void* dst, size_t bytes, int workgroups, hipStream_t s);
 int partial_mfma_occupancy();   // resident workgroups per CU (from the HIP occupancy query)
 int partial_valu_occupancy();
-constexpr int kMfmaWorkersPerGroup = 4;   // independent wavefronts per workgroup of the matrix-core kernel
+int partial_mfma_workers_per_group();     // independent wavefronts per workgroup of the matrix-core kernel
+constexpr int kMaxWorkersPerGroup = 8;
 
 }  // namespace gqa

@@ -2,10 +2,13 @@
 //
 // Every wavefront is an independent persistent worker: it owns one share of the
 // stream split described in gqa_internal.h (or takes shares in turn when the
-// share length is fixed), walks its 32-token tiles in order and keeps the next
-// tile -- or the first tile of the next piece -- in flight in a second register
-// buffer while the current one is computed.  No LDS, no barrier: the partial
-// result of a piece goes from the accumulators straight to the workspace.
+// share length is fixed) and walks its 32-token tiles in order.  One tile (16
+// loads of 16 bytes per lane) is in flight per wavefront: the K registers are
+// refilled with the next tile's K as soon as the scores are computed, the V
+// registers after P.V, so the load stream never drains and never holds more
+// than one tile per wavefront (measured: deeper prefetch lowers the achieved
+// HBM bandwidth on this chip).  No LDS, no barrier: the partial result of a
+// piece goes from the accumulators straight to the workspace.
 // For one tile:
 //
 //   S^T[tok, head] = K[tok, :] . Q[head, :]      v_mfma_f32_16x16x32_bf16, A = K, B = Q^T
@@ -30,6 +33,21 @@
 //     O[head i][32kb + 8r + x].
 #include "gqa_internal.h"
 
+// Compile-time tunables (defaults are the measured best on MI355X: one wavefront per SIMD;
+// more resident wavefronts put more requests in flight and lower the achieved HBM bandwidth).
+#ifndef GQA_MFMA_WGS_PER_CU          // persistent workgroups launched per CU (register budget follows)
+#define GQA_MFMA_WGS_PER_CU 1
+#endif
+#ifndef GQA_MFMA_WAVES               // wavefronts (independent workers) per workgroup
+#define GQA_MFMA_WAVES 4
+#endif
+#ifndef GQA_STREAM_NT                // 1: K and V are read with non-temporal loads
+#define GQA_STREAM_NT 1
+#endif
+#ifndef GQA_MFMA_EARLY_K             // 1: request the next K tile right after the scores, 0: after P.V
+#define GQA_MFMA_EARLY_K 1
+#endif
+
 namespace gqa {
 
 namespace {
@@ -42,8 +60,12 @@ typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
 // K and V are streamed once: non-temporal loads keep them from displacing anything in the caches.
 __device__ __forceinline__ uint4 load_stream16(const uint16_t* p) {
+#if GQA_STREAM_NT
     const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
     return make_uint4(v.x, v.y, v.z, v.w);
+#else
+    return *reinterpret_cast<const uint4*>(p);
+#endif
 }
 
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
@@ -58,41 +80,57 @@ __device__ __forceinline__ f32x4 mfma16(const uint4& a, const uint4& b, const f3
                                                    __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
-struct Tile {            // one 32-token tile in registers
-    uint4 k[2][4];       // [half][mfma step]
-    uint4 v[8];          // [contraction slot e]
-};
-
 struct Piece {           // the part of a share inside one (b, g) row; uniform over the wavefront
     int b, g, tile0, n, len;
 };
 
+struct TileAddr {        // where one 32-token tile of a piece lives; lane-specific row offsets
+    const uint16_t* k[2];    // row of token 16*hf + i, columns 8*kb..
+    const uint16_t* v[2];    // row of token 16*hf + 4*kb, columns 8*i.. (rows +e4 follow at v_stride_t)
+    int vrows[2];            // valid rows among the 4 of each half (for clamping)
+};
+
+// K as the A operand: lane (i, kb) holds columns 8*(4j+kb)+e of token 16*hf + i.
 template <bool PAGED>
-__device__ __forceinline__ void load_tile(const KernelArgs& a, const Piece& p, int tile, int i, int kb, Tile& t) {
+__device__ __forceinline__ void load_k(const KernelArgs& a, const Piece& p, int tile, int i, int kb, uint4 (&k)[2][4]) {
     const int tok0 = kTileTokens * (p.tile0 + tile);
     const int last = p.len - 1;
-    int64_t krow[2], vrow[2];
+    const int tmask = PAGED ? (a.page_size - 1) : 0x7fffffff;
     for (int hf = 0; hf < 2; ++hf) {
+        int64_t row;
         if (PAGED) {
             const int tu = min(tok0 + 16 * hf, last);         // wave-uniform: one page per 16-token half
             const int64_t blk = __builtin_amdgcn_readfirstlane(
                 a.block_table[(int64_t)p.b * a.block_table_stride + (tu >> a.page_shift)]);
-            krow[hf] = blk * a.k_stride_b + (int64_t)p.g * a.k_stride_h;
-            vrow[hf] = blk * a.v_stride_b + (int64_t)p.g * a.v_stride_h;
+            row = blk * a.k_stride_b + (int64_t)p.g * a.k_stride_h;
         } else {
-            krow[hf] = (int64_t)p.b * a.k_stride_b + (int64_t)p.g * a.k_stride_h;
-            vrow[hf] = (int64_t)p.b * a.v_stride_b + (int64_t)p.g * a.v_stride_h;
+            row = (int64_t)p.b * a.k_stride_b + (int64_t)p.g * a.k_stride_h;
         }
+        const int tk = min(tok0 + 16 * hf + i, last);         // masked rows re-read the last valid row
+        const uint16_t* kp = a.k + row + (int64_t)(tk & tmask) * a.k_stride_t + 8 * kb;
+        for (int j = 0; j < 4; ++j) k[hf][j] = load_stream16(kp + 32 * j);
     }
+}
+
+// V rows of the lane's contraction slots: slot e <-> token 16*(e/4) + 4kb + e%4, 16-byte piece i.
+template <bool PAGED>
+__device__ __forceinline__ void load_v(const KernelArgs& a, const Piece& p, int tile, int i, int kb, uint4 (&v)[8]) {
+    const int tok0 = kTileTokens * (p.tile0 + tile);
+    const int last = p.len - 1;
     const int tmask = PAGED ? (a.page_size - 1) : 0x7fffffff;
     for (int hf = 0; hf < 2; ++hf) {
-        const int tk = min(tok0 + 16 * hf + i, last);         // masked rows re-read the last valid row
-        const uint16_t* kp = a.k + krow[hf] + (int64_t)(tk & tmask) * a.k_stride_t + 8 * kb;
-        for (int j = 0; j < 4; ++j) t.k[hf][j] = load_stream16(kp + 32 * j);
+        int64_t row;
+        if (PAGED) {
+            const int tu = min(tok0 + 16 * hf, last);
+            const int64_t blk = __builtin_amdgcn_readfirstlane(
+                a.block_table[(int64_t)p.b * a.block_table_stride + (tu >> a.page_shift)]);
+            row = blk * a.v_stride_b + (int64_t)p.g * a.v_stride_h;
+        } else {
+            row = (int64_t)p.b * a.v_stride_b + (int64_t)p.g * a.v_stride_h;
+        }
         for (int e4 = 0; e4 < 4; ++e4) {
             const int tv = min(tok0 + 16 * hf + 4 * kb + e4, last);
-            const uint16_t* vp = a.v + vrow[hf] + (int64_t)(tv & tmask) * a.v_stride_t + 8 * i;
-            t.v[4 * hf + e4] = load_stream16(vp);
+            v[4 * hf + e4] = load_stream16(a.v + row + (int64_t)(tv & tmask) * a.v_stride_t + 8 * i);
         }
     }
 }
@@ -106,6 +144,13 @@ __device__ __forceinline__ void load_q(const KernelArgs& a, const Piece& p, int 
     }
 }
 
+// Makes the compiler wait for Q here, outside the tile loop: otherwise the wait for the (rarely
+// reloaded) Q registers lands on the loop's first MFMA and also waits for the K/V tile just requested.
+__device__ __forceinline__ void settle_q(uint4 (&qf)[4]) {
+    for (int j = 0; j < 4; ++j)
+        asm volatile("" : "+v"(qf[j].x), "+v"(qf[j].y), "+v"(qf[j].z), "+v"(qf[j].w));
+}
+
 struct SoftmaxState {
     f32x4 acc[8];        // O^T: M-tile x, register r -> O[head i][32kb + 8r + x]
     float m, l;          // running maximum (log2 domain) and this lane's share of the normaliser
@@ -117,14 +162,16 @@ __device__ __forceinline__ void reset(SoftmaxState& st) {
     st.l = 0.f;
 }
 
-__device__ __forceinline__ void compute_tile(const Tile& t, const uint4 (&qf)[4], SoftmaxState& st,
-                                             int tok0, int len, int kb, float c) {
-    // scores: two 16-token halves, contraction over the 128 columns in 4 steps
-    f32x4 s[2];
+// scores of one tile: two 16-token halves, contraction over the 128 columns in 4 steps
+__device__ __forceinline__ void scores(const uint4 (&k)[2][4], const uint4 (&qf)[4], f32x4 (&s)[2]) {
     for (int hf = 0; hf < 2; ++hf) {
         s[hf] = (f32x4){0.f, 0.f, 0.f, 0.f};
-        for (int j = 0; j < 4; ++j) s[hf] = mfma16(t.k[hf][j], qf[j], s[hf]);
+        for (int j = 0; j < 4; ++j) s[hf] = mfma16(k[hf][j], qf[j], s[hf]);
     }
+}
+
+// online softmax update; returns the bf16 probabilities as the B operand of P.V
+__device__ __forceinline__ uint4 softmax_update(const f32x4 (&s)[2], SoftmaxState& st, int tok0, int len, int kb, float c) {
     float sv[8];
     float tmax = -INFINITY;
     for (int hf = 0; hf < 2; ++hf)
@@ -143,18 +190,20 @@ __device__ __forceinline__ void compute_tile(const Tile& t, const uint4 (&qf)[4]
         for (int x = 0; x < 8; ++x) st.acc[x] *= alpha;
         st.m = mn;
     }
+    float pr[8];
+    for (int e = 0; e < 8; ++e) pr[e] = exp2f(sv[e] - st.m);
     uint4 pb;
-    {
-        float pr[8];
-        for (int e = 0; e < 8; ++e) pr[e] = exp2f(sv[e] - st.m);
-        pb.x = pack_bf16(pr[0], pr[1]); pb.y = pack_bf16(pr[2], pr[3]);
-        pb.z = pack_bf16(pr[4], pr[5]); pb.w = pack_bf16(pr[6], pr[7]);
-        // the normaliser sums the rounded weights, so the rounding cancels in O / l
-        st.l += (bf16_lo(pb.x) + bf16_hi(pb.x)) + (bf16_lo(pb.y) + bf16_hi(pb.y)) +
-                (bf16_lo(pb.z) + bf16_hi(pb.z)) + (bf16_lo(pb.w) + bf16_hi(pb.w));
-    }
-    // V^T operands: 8x8 transpose of 16-bit elements, then one MFMA per M-tile
-    const uint32_t* v0 = reinterpret_cast<const uint32_t*>(&t.v[0]);
+    pb.x = pack_bf16(pr[0], pr[1]); pb.y = pack_bf16(pr[2], pr[3]);
+    pb.z = pack_bf16(pr[4], pr[5]); pb.w = pack_bf16(pr[6], pr[7]);
+    // the normaliser sums the rounded weights, so the rounding cancels in O / l
+    st.l += (bf16_lo(pb.x) + bf16_hi(pb.x)) + (bf16_lo(pb.y) + bf16_hi(pb.y)) +
+            (bf16_lo(pb.z) + bf16_hi(pb.z)) + (bf16_lo(pb.w) + bf16_hi(pb.w));
+    return pb;
+}
+
+// O^T += V^T P^T: 8x8 transpose of 16-bit elements in registers, then one MFMA per M-tile
+__device__ __forceinline__ void weighted_values(const uint4 (&v)[8], const uint4& pb, SoftmaxState& st) {
+    const uint32_t* v0 = reinterpret_cast<const uint32_t*>(&v[0]);
     for (int x2 = 0; x2 < 4; ++x2) {
         uint4 even, odd;
         uint32_t* pe = reinterpret_cast<uint32_t*>(&even);
@@ -205,12 +254,12 @@ __device__ __forceinline__ Piece next_piece(const KernelArgs& a, const Piece& p,
 }
 
 template <bool PAGED>
-__global__ __launch_bounds__(kThreads, 2) void partial_mfma_kernel(KernelArgs a) {
+__global__ __launch_bounds__(64 * GQA_MFMA_WAVES, GQA_MFMA_WGS_PER_CU) void partial_mfma_kernel(KernelArgs a) {
     const int lane = threadIdx.x & 63;
     const int i = lane & 15, kb = lane >> 4;
     const float c = a.scale_log2e;
-    const int worker = __builtin_amdgcn_readfirstlane(blockIdx.x * kMfmaWorkersPerGroup + (threadIdx.x >> 6));
-    const int workers = gridDim.x * kMfmaWorkersPerGroup;
+    const int worker = __builtin_amdgcn_readfirstlane(blockIdx.x * GQA_MFMA_WAVES + (threadIdx.x >> 6));
+    const int workers = gridDim.x * GQA_MFMA_WAVES;
 
     const int total = __builtin_amdgcn_readfirstlane(wave_stream_total(a));
     const int share_tiles = share_tiles_for(total, a.fixed_share_tiles, workers);
@@ -231,22 +280,20 @@ __global__ __launch_bounds__(kThreads, 2) void partial_mfma_kernel(KernelArgs a)
         p.len = clamped_len(a, p.b);
         p.n = min(tiles_of(p.len) - p.tile0, end - pos);
 
-        Tile bufA, bufB;
-        uint4 qf[4];
+        uint4 kreg[2][4], vreg[8], qf[4];
         SoftmaxState st;
-        load_tile<PAGED>(a, p, 0, i, kb, bufA);
+        load_k<PAGED>(a, p, 0, i, kb, kreg);
+        load_v<PAGED>(a, p, 0, i, kb, vreg);
         load_q(a, p, i, kb, qf);
         reset(st);
         bool has_next = pos + p.n < end;
         Piece q = has_next ? next_piece(a, p, end - pos - p.n) : p;
-        int t = 0;                       // tile of p held (or arriving) in the current buffer
+        int t = 0;                       // tile of p held (or arriving) in kreg / vreg
+        settle_q(qf);
 
-        // One step: start the load of the tile after (p, t) into `nxt`, compute (p, t) from `cur`,
-        // close the piece if that was its last tile.  Returns false when the share is finished.
-        // The load is issued unconditionally -- when nothing follows it re-reads the current
-        // tile -- so that the number of loads in flight is the same on every path and the
-        // wait before the compute covers `cur` only, never the tile just requested.
-        auto step = [&](const Tile& cur, Tile& nxt) -> bool {
+        while (true) {
+            // the tile after (p, t); when nothing follows, the current tile is requested again so
+            // that the number of loads in flight is the same on every path
             const bool last_of_piece = t + 1 == p.n;
             const bool cross = last_of_piece && has_next;
             Piece ld;
@@ -255,11 +302,23 @@ __global__ __launch_bounds__(kThreads, 2) void partial_mfma_kernel(KernelArgs a)
             ld.tile0 = cross ? q.tile0 : p.tile0;
             ld.len = cross ? q.len : p.len;
             ld.n = 0;
-            load_tile<PAGED>(a, ld, cross ? 0 : (last_of_piece ? t : t + 1), i, kb, nxt);
-            compute_tile(cur, qf, st, kTileTokens * (p.tile0 + t), p.len, kb, c);
-            if (!last_of_piece) { ++t; return true; }
+            const int ldt = cross ? 0 : (last_of_piece ? t : t + 1);
+
+            f32x4 s[2];
+            scores(kreg, qf, s);
+#if GQA_MFMA_EARLY_K
+            load_k<PAGED>(a, ld, ldt, i, kb, kreg);          // the K registers are free again
+#endif
+            const uint4 pb = softmax_update(s, st, kTileTokens * (p.tile0 + t), p.len, kb, c);
+            weighted_values(vreg, pb, st);
+#if !GQA_MFMA_EARLY_K
+            load_k<PAGED>(a, ld, ldt, i, kb, kreg);
+#endif
+            load_v<PAGED>(a, ld, ldt, i, kb, vreg);
+
+            if (!last_of_piece) { ++t; continue; }
             emit_piece(a, p, share, st, i, kb);
-            if (!has_next) return false;
+            if (!has_next) break;
             pos += p.n;
             p = q;
             t = 0;
@@ -267,11 +326,7 @@ __global__ __launch_bounds__(kThreads, 2) void partial_mfma_kernel(KernelArgs a)
             reset(st);
             has_next = pos + p.n < end;
             if (has_next) q = next_piece(a, p, end - pos - p.n);
-            return true;
-        };
-        while (true) {
-            if (!step(bufA, bufB)) break;
-            if (!step(bufB, bufA)) break;
+            settle_q(qf);
         }
     }
 }
@@ -280,17 +335,19 @@ __global__ __launch_bounds__(kThreads, 2) void partial_mfma_kernel(KernelArgs a)
 
 hipError_t launch_partial_mfma(const KernelArgs& a, int workgroups, hipStream_t s) {
     if (a.page_size == 0)
-        hipLaunchKernelGGL(partial_mfma_kernel<false>, dim3(workgroups), dim3(kThreads), 0, s, a);
+        hipLaunchKernelGGL(partial_mfma_kernel<false>, dim3(workgroups), dim3(64 * GQA_MFMA_WAVES), 0, s, a);
     else
-        hipLaunchKernelGGL(partial_mfma_kernel<true>, dim3(workgroups), dim3(kThreads), 0, s, a);
+        hipLaunchKernelGGL(partial_mfma_kernel<true>, dim3(workgroups), dim3(64 * GQA_MFMA_WAVES), 0, s, a);
     return hipGetLastError();
 }
 
 int partial_mfma_occupancy() {
     int n = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, partial_mfma_kernel<false>, kThreads, 0) != hipSuccess || n < 1)
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, partial_mfma_kernel<false>, 64 * GQA_MFMA_WAVES, 0) != hipSuccess || n < 1)
         n = 1;
-    return n;
+    return n < GQA_MFMA_WGS_PER_CU ? n : GQA_MFMA_WGS_PER_CU;
 }
+
+int partial_mfma_workers_per_group() { return GQA_MFMA_WAVES; }
 
 }  // namespace gqa

@@ -71,7 +71,7 @@ def test_workspace_size_covers_all_partials(lib):
 
 @pytest.mark.parametrize("kw,code", [
     (dict(batch=0), -1), (dict(num_q_heads=41), -1), (dict(max_kv_len=-1), -1),
-    (dict(chunk_tokens=96), -1), (dict(kernel_variant=7), -1), (dict(scale=float("nan")), -1),
+    (dict(chunk_tokens=48), -1), (dict(kernel_variant=7), -1), (dict(scale=float("nan")), -1),
     (dict(head_dim=64), -2), (dict(num_q_heads=8 * 17), -2), (dict(page_size=24), -2),
     (dict(page_size=8), -2), (dict(num_q_heads=8 * 16, kernel_variant=1), -2),
     (dict(page_size=16, block_table_stride=10), -1),
