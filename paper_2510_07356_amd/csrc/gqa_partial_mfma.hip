@@ -92,9 +92,10 @@ struct TileAddr {        // where one 32-token tile of a piece lives; lane-speci
 
 // K as the A operand: lane (i, kb) holds columns 8*(4j+kb)+e of token 16*hf + i.
 template <bool PAGED>
-__device__ __forceinline__ void load_k(const KernelArgs& a, const Piece& p, int tile, int i, int kb, uint4 (&k)[2][4]) {
+__device__ __forceinline__ void load_k(const KernelArgs& a, const Piece& p, int tile, bool idle, int i, int kb,
+                                       uint4 (&k)[2][4]) {
     const int tok0 = kTileTokens * (p.tile0 + tile);
-    const int last = p.len - 1;
+    const int last = idle ? tok0 : p.len - 1;     // idle: every lane re-reads row tok0, one cache line per load
     const int tmask = PAGED ? (a.page_size - 1) : 0x7fffffff;
     for (int hf = 0; hf < 2; ++hf) {
         int64_t row;
@@ -107,16 +108,17 @@ __device__ __forceinline__ void load_k(const KernelArgs& a, const Piece& p, int 
             row = (int64_t)p.b * a.k_stride_b + (int64_t)p.g * a.k_stride_h;
         }
         const int tk = min(tok0 + 16 * hf + i, last);         // masked rows re-read the last valid row
-        const uint16_t* kp = a.k + row + (int64_t)(tk & tmask) * a.k_stride_t + 8 * kb;
-        for (int j = 0; j < 4; ++j) k[hf][j] = load_stream16(kp + 32 * j);
+        const uint16_t* kp = a.k + row + (int64_t)(tk & tmask) * a.k_stride_t + (idle ? 0 : 8 * kb);
+        for (int j = 0; j < 4; ++j) k[hf][j] = load_stream16(kp + (idle ? 0 : 32 * j));
     }
 }
 
 // V rows of the lane's contraction slots: slot e <-> token 16*(e/4) + 4kb + e%4, 16-byte piece i.
 template <bool PAGED>
-__device__ __forceinline__ void load_v(const KernelArgs& a, const Piece& p, int tile, int i, int kb, uint4 (&v)[8]) {
+__device__ __forceinline__ void load_v(const KernelArgs& a, const Piece& p, int tile, bool idle, int i, int kb,
+                                       uint4 (&v)[8]) {
     const int tok0 = kTileTokens * (p.tile0 + tile);
-    const int last = p.len - 1;
+    const int last = idle ? tok0 : p.len - 1;
     const int tmask = PAGED ? (a.page_size - 1) : 0x7fffffff;
     for (int hf = 0; hf < 2; ++hf) {
         int64_t row;
@@ -130,7 +132,7 @@ __device__ __forceinline__ void load_v(const KernelArgs& a, const Piece& p, int 
         }
         for (int e4 = 0; e4 < 4; ++e4) {
             const int tv = min(tok0 + 16 * hf + 4 * kb + e4, last);
-            v[4 * hf + e4] = load_stream16(a.v + row + (int64_t)(tv & tmask) * a.v_stride_t + 8 * i);
+            v[4 * hf + e4] = load_stream16(a.v + row + (int64_t)(tv & tmask) * a.v_stride_t + (idle ? 0 : 8 * i));
         }
     }
 }
@@ -282,8 +284,8 @@ __global__ __launch_bounds__(64 * GQA_MFMA_WAVES, GQA_MFMA_WGS_PER_CU) void part
 
         uint4 kreg[2][4], vreg[8], qf[4];
         SoftmaxState st;
-        load_k<PAGED>(a, p, 0, i, kb, kreg);
-        load_v<PAGED>(a, p, 0, i, kb, vreg);
+        load_k<PAGED>(a, p, 0, false, i, kb, kreg);
+        load_v<PAGED>(a, p, 0, false, i, kb, vreg);
         load_q(a, p, i, kb, qf);
         reset(st);
         bool has_next = pos + p.n < end;
@@ -292,10 +294,12 @@ __global__ __launch_bounds__(64 * GQA_MFMA_WAVES, GQA_MFMA_WGS_PER_CU) void part
         settle_q(qf);
 
         while (true) {
-            // the tile after (p, t); when nothing follows, the current tile is requested again so
-            // that the number of loads in flight is the same on every path
+            // the tile after (p, t); when nothing follows, one row of the current tile is requested
+            // again by all lanes (a single cache line) so that the number of loads in flight is
+            // the same on every path and the waits in the loop never cover the tile just requested
             const bool last_of_piece = t + 1 == p.n;
             const bool cross = last_of_piece && has_next;
+            const bool idle = last_of_piece && !has_next;
             Piece ld;
             ld.b = cross ? q.b : p.b;
             ld.g = cross ? q.g : p.g;
@@ -307,14 +311,14 @@ __global__ __launch_bounds__(64 * GQA_MFMA_WAVES, GQA_MFMA_WGS_PER_CU) void part
             f32x4 s[2];
             scores(kreg, qf, s);
 #if GQA_MFMA_EARLY_K
-            load_k<PAGED>(a, ld, ldt, i, kb, kreg);          // the K registers are free again
+            load_k<PAGED>(a, ld, ldt, idle, i, kb, kreg);    // the K registers are free again
 #endif
             const uint4 pb = softmax_update(s, st, kTileTokens * (p.tile0 + t), p.len, kb, c);
             weighted_values(vreg, pb, st);
 #if !GQA_MFMA_EARLY_K
-            load_k<PAGED>(a, ld, ldt, i, kb, kreg);
+            load_k<PAGED>(a, ld, ldt, idle, i, kb, kreg);
 #endif
-            load_v<PAGED>(a, ld, ldt, i, kb, vreg);
+            load_v<PAGED>(a, ld, ldt, idle, i, kb, vreg);
 
             if (!last_of_piece) { ++t; continue; }
             emit_piece(a, p, share, st, i, kb);
