@@ -26,6 +26,29 @@ HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published peak
 EVENT_STRIDE = 4            # one step in four records HIP events around its kernels
 
 
+def measured_traffic(config_index: int):
+    """HBM bytes per launch of the partial kernel from the committed counter summary, or None when
+    the kernel sources have changed since the counters were taken."""
+    import glob
+    import hashlib
+    path = os.path.join(ROOT, "profiles", "partial_mfma_kernel_hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    kv = {}
+    for line in open(path):
+        if "=" in line and not line.startswith("#"):
+            k, v = line.split("=", 1)
+            kv[k.strip()] = v.strip()
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2510_07356_amd", "csrc", "*"))):
+        h.update(os.path.basename(f).encode())
+        h.update(open(f, "rb").read())
+    if kv.get("source_sha256") != h.hexdigest():
+        return None
+    v = kv.get(f"config{config_index}_partial_traffic_bytes")
+    return int(v) if v is not None else None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -133,7 +156,8 @@ def main() -> int:
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBPS, 4),
-            "traffic": None,
+            "traffic": measured_traffic(args.config) if (args.variant == 0 and args.chunk == 0
+                                                         and args.layout == "head_major") else None,
         },
     }
 
