@@ -132,7 +132,7 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16 in, fp32 accumulate",
+        "dtype": "bf16",
         "data": "synthetic",
         "config": {
             "workload": f"{w.name} (configs[{args.config}]): B={w.batch} Hq={w.num_q_heads} Hkv={w.num_kv_heads} "

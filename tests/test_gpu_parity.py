@@ -140,6 +140,85 @@ def test_strided_q_and_no_lse(binding):
     check(w, out, None, ref, "strided_q")
 
 
+def test_many_short_sequences_with_gaps(binding):
+    """More sequences than lanes in a wavefront (the stream positions are found by a multi-pass
+    wave scan), empty sequences at the start, in runs in the middle and at the end."""
+    rng = np.random.default_rng(7)
+    lens = rng.integers(0, 200, size=300)
+    lens[:3] = 0
+    lens[100:140] = 0
+    lens[-2:] = 0
+    lens[150] = 3000
+    for paged in (False, True):
+        if paged:
+            w = wl.make_paged("many_paged", 107, 300, 16, 4, lens, table_width=3000 // 16 + 1)
+        else:
+            w = wl.make_contiguous("many", 107, 300, 16, 4, lens)
+        ref = oracle_of(w)
+        for variant, chunk in ((0, 0), (0, 32), (0, 4096), (1, 0), (1, 96)):
+            out, lse = binding.run_workload(w, chunk_tokens=chunk, kernel_variant=variant)
+            check(w, out, lse, ref, f"{w.name}/v{variant}/c{chunk}")
+
+
+def test_all_sequences_empty(binding):
+    w = wl.make_contiguous("all_empty", 108, 5, 40, 8, [0] * 5, cache_len=64)
+    for variant in (0, 1):
+        out, lse = binding.run_workload(w, kernel_variant=variant)
+        assert bool((out == 0).all()) and bool(np.isneginf(lse.cpu().numpy()).all())
+
+
+def test_group_of_sixteen_paged(binding):
+    w = wl.make_paged("g16_paged", 109, 3, 32, 2, [700, 15, 130], page_size=32, table_width=24)
+    check(w, *binding.run_workload(w), oracle_of(w), "g16_paged")
+
+
+def test_device_lengths_are_clamped_to_the_bound(binding):
+    """A device-side length above max_kv_len is read as max_kv_len (no read past the bound)."""
+    import torch
+    w = wl.make_contiguous("clamp", 110, 2, 40, 8, [300, 250], cache_len=300)
+    dev = binding.to_device(w)
+    dev["kv_lens"] = torch.tensor([300, 1000], dtype=torch.int32, device="cuda:0")   # stale, too long
+    q, k, v = dev["q"], dev["k"], dev["v"]
+    params = binding.make_params(q, k, v, 250, w.scale)                               # bound: 250
+    ws = torch.full((binding.gqa_decode_workspace_bytes(params),), 0xFF, dtype=torch.uint8, device="cuda:0")
+    out = torch.empty((2, 40, 128), dtype=torch.float32, device="cuda:0")
+    binding.gqa_decode_attn(params, q, k, v, dev["kv_lens"], None, None, out, None, ws)
+    w.kv_lens = np.array([250, 250], dtype=np.int32)                                  # what the oracle is given
+    check(w, out, None, oracle_of(w), "clamp")
+
+
+def test_workspace_reuse_and_side_stream(binding):
+    """One poisoned workspace serves two different calls in a row; the second runs on a side stream."""
+    import torch
+    wa = wl.make_contiguous("reuse_a", 111, 4, 40, 8, [900, 64, 2000, 1])
+    wb = wl.make_paged("reuse_b", 112, 6, 32, 8, [33, 500, 16, 1200, 0, 80], table_width=80)
+    da, db = binding.to_device(wa), binding.to_device(wb)
+    pa = binding.make_params(da["q"], da["k"], da["v"], wa.max_kv_len, wa.scale)
+    pb = binding.make_params(db["q"], db["k"], db["v"], wb.max_kv_len, wb.scale, wb.page_size, db["block_table"])
+    nbytes = max(binding.gqa_decode_workspace_bytes(pa), binding.gqa_decode_workspace_bytes(pb))
+    ws = torch.full((nbytes,), 0xFF, dtype=torch.uint8, device="cuda:0")
+    oa = torch.empty((4, 40, 128), dtype=torch.float32, device="cuda:0")
+    ob = torch.empty((6, 32, 128), dtype=torch.float32, device="cuda:0")
+    la = torch.empty((4, 40), dtype=torch.float32, device="cuda:0")
+    lb = torch.empty((6, 32), dtype=torch.float32, device="cuda:0")
+    binding.gqa_decode_attn(pa, da["q"], da["k"], da["v"], da["kv_lens"], None, None, oa, la, ws)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        binding.gqa_decode_attn(pb, db["q"], db["k"], db["v"], db["kv_lens"], db["block_table"], wb.kv_lens,
+                                ob, lb, ws, stream=side)
+    side.synchronize()
+    check(wa, oa, la, oracle_of(wa), "reuse_a")
+    check(wb, ob, lb, oracle_of(wb), "reuse_b/side_stream")
+
+
+def test_timer_reports_both_kernels(binding):
+    w = wl.make_contiguous("timer", 113, 8, 40, 8, [4096] * 8)
+    out, lse, ms = binding.run_workload(w, timed=True)
+    assert len(ms) == 2 and all(0.0 < x < 50.0 for x in ms)
+    check(w, out, lse, oracle_of(w), "timer")
+
+
 # --------------------------------------------------------------------------- the five configurations, full size
 
 @pytest.mark.parametrize("index", [0, 1, 2, 3, 4])
