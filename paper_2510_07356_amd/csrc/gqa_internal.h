@@ -53,6 +53,18 @@ struct KernelArgs {
 __device__ __forceinline__ int clamped_len(const KernelArgs& a, int b) {
     return min(max(a.kv_lens[b], 0), a.max_kv_len);
 }
+
+// Read-only int32 at a wavefront-uniform index through the scalar data path (constant address
+// space): the value lands in an SGPR and the load is tracked by lgkmcnt, so it neither occupies a
+// slot among the K/V vector loads in flight nor forces a wait on them.  Only for arrays the kernel
+// never writes (kv_lens, block_table).
+__device__ __forceinline__ int uniform_i32(const int32_t* base, int64_t index) {
+    typedef const __attribute__((address_space(4))) int32_t* const_ptr;
+    return reinterpret_cast<const_ptr>(reinterpret_cast<uintptr_t>(base))[index];
+}
+__device__ __forceinline__ int uniform_len(const KernelArgs& a, int b) {
+    return min(max(uniform_i32(a.kv_lens, b), 0), a.max_kv_len);
+}
 __host__ __device__ __forceinline__ int tiles_of(int len) { return (len + kTileTokens - 1) / kTileTokens; }
 
 __host__ __device__ __forceinline__ int share_tiles_for(int64_t total, int fixed, int workers) {
@@ -95,7 +107,7 @@ __device__ __forceinline__ int stream_total(const KernelArgs& a, int* scratch) {
 // Position in the stream -> (sequence, kv head, tile within the row).  Every thread
 // of the workgroup must call it; the answer is broadcast through `found` (3 ints).
 // If `prefix_out` is given, also writes the stream position of every sequence.
-struct StreamPos { int b, g, tile; };
+struct StreamPos { int b, g, tile, len; };
 
 __device__ __forceinline__ StreamPos stream_locate(const KernelArgs& a, int pos, int* scratch, int* found,
                                                    int32_t* prefix_out) {
@@ -118,6 +130,7 @@ __device__ __forceinline__ StreamPos stream_locate(const KernelArgs& a, int pos,
     __syncthreads();
     StreamPos p;
     p.b = found[0]; p.g = found[1]; p.tile = found[2];
+    p.len = clamped_len(a, p.b);
     return p;
 }
 
@@ -147,10 +160,11 @@ __device__ __forceinline__ StreamPos wave_stream_locate(const KernelArgs& a, int
     const int lane = threadIdx.x & 63;
     int carry = 0;
     StreamPos p;
-    p.b = 0; p.g = 0; p.tile = 0;
+    p.b = 0; p.g = 0; p.tile = 0; p.len = 0;
     for (int base = 0; base < a.batch; base += 64) {
         const int b = base + lane;
-        const int tb = (b < a.batch) ? tiles_of(clamped_len(a, b)) : 0;
+        const int len = (b < a.batch) ? clamped_len(a, b) : 0;
+        const int tb = tiles_of(len);
         const int n = a.num_kv_heads * tb;
         const int incl = wave_scan_incl(n);
         const int excl = carry + incl - n;
@@ -163,6 +177,7 @@ __device__ __forceinline__ StreamPos wave_stream_locate(const KernelArgs& a, int
             p.b = base + src;
             p.g = (pos - ex) / tbs;
             p.tile = (pos - ex) % tbs;
+            p.len = __shfl(len, src);
         }
         carry += __shfl(incl, 63);
     }

@@ -90,23 +90,26 @@ struct TileAddr {        // where one 32-token tile of a piece lives; lane-speci
     int vrows[2];            // valid rows among the 4 of each half (for clamping)
 };
 
+// Physical blocks of the two 16-token halves of a tile (paged caches): each half lies inside one
+// page, so the ids are wave-uniform and come through the scalar path.
+__device__ __forceinline__ void tile_blocks(const KernelArgs& a, const Piece& p, int tile, bool idle, int (&blk)[2]) {
+    const int tok0 = kTileTokens * (p.tile0 + tile);
+    const int last = idle ? tok0 : p.len - 1;
+    for (int hf = 0; hf < 2; ++hf) {
+        const int tu = min(tok0 + 16 * hf, last);
+        blk[hf] = uniform_i32(a.block_table, (int64_t)p.b * a.block_table_stride + (tu >> a.page_shift));
+    }
+}
+
 // K as the A operand: lane (i, kb) holds columns 8*(4j+kb)+e of token 16*hf + i.
 template <bool PAGED>
-__device__ __forceinline__ void load_k(const KernelArgs& a, const Piece& p, int tile, bool idle, int i, int kb,
-                                       uint4 (&k)[2][4]) {
+__device__ __forceinline__ void load_k(const KernelArgs& a, const Piece& p, int tile, bool idle, const int (&blk)[2],
+                                       int i, int kb, uint4 (&k)[2][4]) {
     const int tok0 = kTileTokens * (p.tile0 + tile);
     const int last = idle ? tok0 : p.len - 1;     // idle: every lane re-reads row tok0, one cache line per load
     const int tmask = PAGED ? (a.page_size - 1) : 0x7fffffff;
     for (int hf = 0; hf < 2; ++hf) {
-        int64_t row;
-        if (PAGED) {
-            const int tu = min(tok0 + 16 * hf, last);         // wave-uniform: one page per 16-token half
-            const int64_t blk = __builtin_amdgcn_readfirstlane(
-                a.block_table[(int64_t)p.b * a.block_table_stride + (tu >> a.page_shift)]);
-            row = blk * a.k_stride_b + (int64_t)p.g * a.k_stride_h;
-        } else {
-            row = (int64_t)p.b * a.k_stride_b + (int64_t)p.g * a.k_stride_h;
-        }
+        const int64_t row = (PAGED ? (int64_t)blk[hf] : (int64_t)p.b) * a.k_stride_b + (int64_t)p.g * a.k_stride_h;
         const int tk = min(tok0 + 16 * hf + i, last);         // masked rows re-read the last valid row
         const uint16_t* kp = a.k + row + (int64_t)(tk & tmask) * a.k_stride_t + (idle ? 0 : 8 * kb);
         for (int j = 0; j < 4; ++j) k[hf][j] = load_stream16(kp + (idle ? 0 : 32 * j));
@@ -115,21 +118,13 @@ __device__ __forceinline__ void load_k(const KernelArgs& a, const Piece& p, int 
 
 // V rows of the lane's contraction slots: slot e <-> token 16*(e/4) + 4kb + e%4, 16-byte piece i.
 template <bool PAGED>
-__device__ __forceinline__ void load_v(const KernelArgs& a, const Piece& p, int tile, bool idle, int i, int kb,
-                                       uint4 (&v)[8]) {
+__device__ __forceinline__ void load_v(const KernelArgs& a, const Piece& p, int tile, bool idle, const int (&blk)[2],
+                                       int i, int kb, uint4 (&v)[8]) {
     const int tok0 = kTileTokens * (p.tile0 + tile);
     const int last = idle ? tok0 : p.len - 1;
     const int tmask = PAGED ? (a.page_size - 1) : 0x7fffffff;
     for (int hf = 0; hf < 2; ++hf) {
-        int64_t row;
-        if (PAGED) {
-            const int tu = min(tok0 + 16 * hf, last);
-            const int64_t blk = __builtin_amdgcn_readfirstlane(
-                a.block_table[(int64_t)p.b * a.block_table_stride + (tu >> a.page_shift)]);
-            row = blk * a.v_stride_b + (int64_t)p.g * a.v_stride_h;
-        } else {
-            row = (int64_t)p.b * a.v_stride_b + (int64_t)p.g * a.v_stride_h;
-        }
+        const int64_t row = (PAGED ? (int64_t)blk[hf] : (int64_t)p.b) * a.v_stride_b + (int64_t)p.g * a.v_stride_h;
         for (int e4 = 0; e4 < 4; ++e4) {
             const int tv = min(tok0 + 16 * hf + 4 * kb + e4, last);
             v[4 * hf + e4] = load_stream16(a.v + row + (int64_t)(tv & tmask) * a.v_stride_t + (idle ? 0 : 8 * i));
@@ -249,7 +244,7 @@ __device__ __forceinline__ Piece next_piece(const KernelArgs& a, const Piece& p,
     q.g = p.g + 1;
     if (q.g == a.num_kv_heads) {
         q.g = 0;
-        do { ++q.b; q.len = clamped_len(a, q.b); } while (q.len == 0 && q.b + 1 < a.batch);
+        do { ++q.b; q.len = uniform_len(a, q.b); } while (q.len == 0 && q.b + 1 < a.batch);
     }
     q.n = min(tiles_of(q.len), left);
     return q;
@@ -279,13 +274,16 @@ __global__ __launch_bounds__(64 * GQA_MFMA_WAVES, GQA_MFMA_WGS_PER_CU) void part
         p.b = __builtin_amdgcn_readfirstlane(sp.b);
         p.g = __builtin_amdgcn_readfirstlane(sp.g);
         p.tile0 = __builtin_amdgcn_readfirstlane(sp.tile);
-        p.len = clamped_len(a, p.b);
+        p.len = __builtin_amdgcn_readfirstlane(sp.len);
         p.n = min(tiles_of(p.len) - p.tile0, end - pos);
 
         uint4 kreg[2][4], vreg[8], qf[4];
         SoftmaxState st;
-        load_k<PAGED>(a, p, 0, false, i, kb, kreg);
-        load_v<PAGED>(a, p, 0, false, i, kb, vreg);
+        int blk[2] = {0, 0}, blk_ahead[2] = {0, 0};      // paged: blocks of the tile being requested / the one after
+        bool ahead_valid = false;
+        if (PAGED) tile_blocks(a, p, 0, false, blk);
+        load_k<PAGED>(a, p, 0, false, blk, i, kb, kreg);
+        load_v<PAGED>(a, p, 0, false, blk, i, kb, vreg);
         load_q(a, p, i, kb, qf);
         reset(st);
         bool has_next = pos + p.n < end;
@@ -308,17 +306,25 @@ __global__ __launch_bounds__(64 * GQA_MFMA_WAVES, GQA_MFMA_WGS_PER_CU) void part
             ld.n = 0;
             const int ldt = cross ? 0 : (last_of_piece ? t : t + 1);
 
+            if (PAGED) {
+                // block ids of the tile requested now: fetched one step ahead inside a piece
+                if (ahead_valid && !last_of_piece) { blk[0] = blk_ahead[0]; blk[1] = blk_ahead[1]; }
+                else tile_blocks(a, ld, ldt, idle, blk);
+                ahead_valid = t + 2 < p.n;
+                if (ahead_valid) tile_blocks(a, p, t + 2, false, blk_ahead);
+            }
+
             f32x4 s[2];
             scores(kreg, qf, s);
 #if GQA_MFMA_EARLY_K
-            load_k<PAGED>(a, ld, ldt, idle, i, kb, kreg);    // the K registers are free again
+            load_k<PAGED>(a, ld, ldt, idle, blk, i, kb, kreg);    // the K registers are free again
 #endif
             const uint4 pb = softmax_update(s, st, kTileTokens * (p.tile0 + t), p.len, kb, c);
             weighted_values(vreg, pb, st);
 #if !GQA_MFMA_EARLY_K
-            load_k<PAGED>(a, ld, ldt, idle, i, kb, kreg);
+            load_k<PAGED>(a, ld, ldt, idle, blk, i, kb, kreg);
 #endif
-            load_v<PAGED>(a, ld, ldt, idle, i, kb, vreg);
+            load_v<PAGED>(a, ld, ldt, idle, blk, i, kb, vreg);
 
             if (!last_of_piece) { ++t; continue; }
             emit_piece(a, p, share, st, i, kb);
@@ -330,6 +336,7 @@ __global__ __launch_bounds__(64 * GQA_MFMA_WAVES, GQA_MFMA_WGS_PER_CU) void part
             reset(st);
             has_next = pos + p.n < end;
             if (has_next) q = next_piece(a, p, end - pos - p.n);
+            ahead_valid = false;
             settle_q(qf);
         }
     }
