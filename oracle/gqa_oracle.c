@@ -32,9 +32,10 @@
  * block_table[b*block_table_stride + j / page_size] at slot j % page_size,
  * i.e. at  base + block*stride_b + g*stride_h + slot*stride_t.
  *
- * Every function here is pinned by tests/test_oracle_pins.py (brute force in
- * exact rational/fsum arithmetic on tiny inputs, closed forms, invariants, a
- * float64 library cross-check).
+ * Every function here is pinned by tests/test_oracle_pins.py (attention: brute
+ * force in fsum arithmetic on tiny inputs, closed forms, invariants, a float64
+ * library cross-check; append/rotary: identity at angle zero, quarter turns,
+ * norm and relative-position invariants, bf16 rounding against exact cases).
  */
 #include <math.h>
 #include <stdint.h>
@@ -163,4 +164,92 @@ int gqa_oracle_decode_attn(const gqa_oracle_shape *s,
         free(score);
     }
     return used;
+}
+
+/* ------------------------------------------------------------------------
+ * Reference for the step that precedes attention in a decode layer: rotate
+ * the new token's query and key by its position (optional) and append the
+ * new key/value rows to the cache at position kv_lens[b] - 1.
+ *
+ * Rotary embedding, "rotate-half" pairing of the 32B model family the paper
+ * samples from: column d < D/2 is paired with column d + D/2,
+ *     x'[d]       = x[d] * cos[pos][d] - x[d + D/2] * sin[pos][d]
+ *     x'[d + D/2] = x[d + D/2] * cos[pos][d] + x[d] * sin[pos][d]
+ * with pos = kv_lens[b] - 1 and the caller's table cos_sin[pos][0..D/2) = cos,
+ * cos_sin[pos][D/2..D) = sin (fp32, widened exactly).  Arithmetic in double,
+ * result rounded to bf16 with round-to-nearest-even.  cos_sin == NULL copies
+ * q and k unchanged.  V is always copied bit for bit.  For a sequence with
+ * kv_lens[b] <= 0 the query is copied unchanged and nothing is written to the
+ * cache.  Cache addressing as in the attention oracle.
+ * ---------------------------------------------------------------------- */
+static uint16_t round_to_bf16(double x)
+{
+    /* double -> float is exact enough here only if we round once: go through
+     * the exact integer representation of the bf16 grid instead. */
+    if (x == 0.0 || isnan(x) || isinf(x)) {
+        float f = (float)x;
+        uint32_t w;
+        memcpy(&w, &f, sizeof w);
+        return (uint16_t)(w >> 16);
+    }
+    int e;
+    double m = frexp(fabs(x), &e);          /* |x| = m * 2^e, m in [0.5, 1) */
+    if (e < -125) {                         /* bf16 subnormal range: fixed spacing 2^-133 */
+        double q = nearbyint(ldexp(fabs(x), 133));
+        float f = (float)ldexp(q, -133);
+        if (x < 0) f = -f;
+        uint32_t w;
+        memcpy(&w, &f, sizeof w);
+        return (uint16_t)(w >> 16);
+    }
+    double q = nearbyint(ldexp(m, 8));      /* 8 significant bits, ties to even (default rounding mode) */
+    float f = (float)ldexp(q, e - 8);
+    if (x < 0) f = -f;
+    uint32_t w;
+    memcpy(&w, &f, sizeof w);
+    return (uint16_t)(w >> 16);
+}
+
+int gqa_oracle_kv_append(const gqa_oracle_shape *s,
+                         const uint16_t *q_in, uint16_t *q_out,          /* [B, Hq, D] via q strides */
+                         const uint16_t *k_new, const uint16_t *v_new,   /* [B, Hkv, D] dense */
+                         uint16_t *k_cache, uint16_t *v_cache,
+                         const int32_t *kv_lens, const int32_t *block_table,
+                         const float *cos_sin)                           /* [positions, D] or NULL */
+{
+    if (!s || !q_in || !q_out || !k_new || !v_new || !k_cache || !v_cache || !kv_lens) return -1;
+    const int D = s->head_dim, half = D / 2;
+    if (D % 2 != 0) return -1;
+    for (int b = 0; b < s->batch; ++b) {
+        const int64_t pos = (int64_t)kv_lens[b] - 1;
+        for (int h = 0; h < s->num_q_heads; ++h) {
+            const uint16_t *src = q_in + (int64_t)b * s->q_stride_b + (int64_t)h * s->q_stride_h;
+            uint16_t *dst = q_out + (int64_t)b * s->q_stride_b + (int64_t)h * s->q_stride_h;
+            for (int d = 0; d < half; ++d) {
+                if (!cos_sin || pos < 0) { dst[d] = src[d]; dst[d + half] = src[d + half]; continue; }
+                const double c = (double)cos_sin[pos * D + d], sn = (double)cos_sin[pos * D + half + d];
+                const double x = widen_bf16(src[d]), y = widen_bf16(src[d + half]);
+                dst[d] = round_to_bf16(x * c - y * sn);
+                dst[d + half] = round_to_bf16(y * c + x * sn);
+            }
+        }
+        if (pos < 0) continue;
+        for (int g = 0; g < s->num_kv_heads; ++g) {
+            const uint16_t *ks = k_new + ((int64_t)b * s->num_kv_heads + g) * D;
+            const uint16_t *vs = v_new + ((int64_t)b * s->num_kv_heads + g) * D;
+            uint16_t *kd = (uint16_t *)token_row(k_cache, s, s->k_stride_b, s->k_stride_h, s->k_stride_t,
+                                                 block_table, b, g, pos);
+            uint16_t *vd = (uint16_t *)token_row(v_cache, s, s->v_stride_b, s->v_stride_h, s->v_stride_t,
+                                                 block_table, b, g, pos);
+            for (int d = 0; d < half; ++d) {
+                if (!cos_sin) { kd[d] = ks[d]; kd[d + half] = ks[d + half]; continue; }
+                const double c = (double)cos_sin[pos * D + d], sn = (double)cos_sin[pos * D + half + d];
+                const double x = widen_bf16(ks[d]), y = widen_bf16(ks[d + half]);
+                kd[d] = round_to_bf16(x * c - y * sn);
+                kd[d + half] = round_to_bf16(y * c + x * sn);
+            }
+            for (int d = 0; d < D; ++d) vd[d] = vs[d];
+        }
+    }
+    return 0;
 }

@@ -52,6 +52,8 @@ def _load():
             ctypes.POINTER(_Shape), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_void_p, ctypes.c_int64, ctypes.c_int]
+        _lib.gqa_oracle_kv_append.restype = ctypes.c_int
+        _lib.gqa_oracle_kv_append.argtypes = [ctypes.POINTER(_Shape)] + [ctypes.c_void_p] * 9
     return _lib
 
 
@@ -129,3 +131,52 @@ def decode_attn(q: np.ndarray, k: np.ndarray, v: np.ndarray, kv_lens: np.ndarray
     if used < 0:
         raise ValueError("oracle rejected its arguments")
     return OracleResult(out=out, lse=lse, weights=w, threads=used)
+
+
+def kv_append(q: np.ndarray, k_new: np.ndarray, v_new: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray,
+              kv_lens: np.ndarray, cos_sin: Optional[np.ndarray] = None,
+              block_table: Optional[np.ndarray] = None, page_size: int = 0) -> np.ndarray:
+    """Rotate q and the new key by position kv_lens[b] - 1 (if cos_sin [positions, D] fp32 is given)
+    and write the new key/value rows into the caches IN PLACE at that position.
+    q [B, Hq, D]; k_new, v_new [B, Hkv, D] dense; caches indexed as in decode_attn.
+    Returns the rotated q (same shape and strides as a dense copy of q)."""
+    lib = _load()
+    q = np.ascontiguousarray(_u16(q))
+    k_new, v_new = np.ascontiguousarray(_u16(k_new)), np.ascontiguousarray(_u16(v_new))
+    k_cache, v_cache = _u16(k_cache), _u16(v_cache)
+    if not (k_cache.flags.writeable and v_cache.flags.writeable):
+        raise ValueError("caches must be writable")
+    B, Hq, D = q.shape
+    Hkv = k_new.shape[1]
+    kv_lens = np.ascontiguousarray(kv_lens, dtype=np.int32)
+    sh = _Shape()
+    sh.batch, sh.num_q_heads, sh.num_kv_heads, sh.head_dim = B, Hq, Hkv, D
+    sh.page_size = int(page_size)
+    sh.q_stride_b, sh.q_stride_h = q.strides[0] // 2, q.strides[1] // 2
+    sh.k_stride_b, sh.k_stride_h, sh.k_stride_t = (x // 2 for x in k_cache.strides[:3])
+    sh.v_stride_b, sh.v_stride_h, sh.v_stride_t = (x // 2 for x in v_cache.strides[:3])
+    bt_ptr = None
+    if page_size:
+        block_table = np.ascontiguousarray(block_table, dtype=np.int32)
+        sh.block_table_stride = block_table.shape[1]
+        bt_ptr = _base_ptr(block_table)
+        for b in range(B):
+            if kv_lens[b] > 0:
+                blk = block_table[b, (int(kv_lens[b]) - 1) // page_size]
+                if blk < 0 or blk >= k_cache.shape[0]:
+                    raise ValueError("block table entry out of range")
+    elif int(kv_lens.max(initial=0)) > k_cache.shape[2]:
+        raise ValueError("kv_lens exceeds the cache length")
+    cs_ptr = None
+    if cos_sin is not None:
+        cos_sin = np.ascontiguousarray(cos_sin, dtype=np.float32)
+        if cos_sin.ndim != 2 or cos_sin.shape[1] != D or cos_sin.shape[0] < int(kv_lens.max(initial=0)):
+            raise ValueError("cos_sin must be [positions >= max kv_len, D]")
+        cs_ptr = _base_ptr(cos_sin)
+    q_out = np.empty_like(q)
+    rc = lib.gqa_oracle_kv_append(ctypes.byref(sh), _base_ptr(q), _base_ptr(q_out), _base_ptr(k_new),
+                                  _base_ptr(v_new), _base_ptr(k_cache), _base_ptr(v_cache),
+                                  _base_ptr(kv_lens), bt_ptr, cs_ptr)
+    if rc != 0:
+        raise ValueError("oracle rejected its arguments")
+    return q_out

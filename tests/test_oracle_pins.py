@@ -363,3 +363,158 @@ def test_thread_count_does_not_change_the_result():
     c = decode_attn(w.q, w.k, w.v, w.kv_lens, w.scale, threads=4)
     np.testing.assert_array_equal(a.out, c.out)
     assert a.threads == 1 and 1 <= c.threads <= 4
+
+
+# --------------------------------------------------------------------------- append + rotary oracle
+
+from oracle import kv_append  # noqa: E402
+
+
+def rope_table(positions, D, theta=1.0e6):
+    """cos/sin of pos * theta^(-2d/D), d < D/2, computed in float64 and stored as fp32 [positions, D]."""
+    d = np.arange(D // 2, dtype=np.float64)
+    ang = np.arange(positions, dtype=np.float64)[:, None] * theta ** (-2.0 * d / D)[None, :]
+    return np.concatenate([np.cos(ang), np.sin(ang)], axis=1).astype(np.float32)
+
+
+def test_append_without_rotary_is_a_bit_exact_scatter():
+    w = make_contiguous("app", 51, 3, 8, 2, [5, 0, 9], head_dim=8, cache_len=10)
+    rng = np.random.default_rng(1)
+    k_new = f32_to_bf16_bits(rng.standard_normal((3, 2, 8)).astype(np.float32))
+    v_new = f32_to_bf16_bits(rng.standard_normal((3, 2, 8)).astype(np.float32))
+    for layout in ("head_major", "token_major"):
+        k, v = w.k.copy(), w.v.copy()
+        if layout == "token_major":
+            k = np.ascontiguousarray(k.transpose(0, 2, 1, 3)).transpose(0, 2, 1, 3)
+            v = np.ascontiguousarray(v.transpose(0, 2, 1, 3)).transpose(0, 2, 1, 3)
+        k0, v0 = k.copy(), v.copy()
+        q_out = kv_append(w.q, k_new, v_new, k, v, w.kv_lens)
+        np.testing.assert_array_equal(q_out, w.q)
+        for b, L in enumerate(w.kv_lens):
+            if L > 0:
+                np.testing.assert_array_equal(k[b, :, L - 1], k_new[b])
+                np.testing.assert_array_equal(v[b, :, L - 1], v_new[b])
+                k0[b, :, L - 1] = k_new[b]
+                v0[b, :, L - 1] = v_new[b]
+        np.testing.assert_array_equal(k, k0)          # nothing else was touched (empty sequence included)
+        np.testing.assert_array_equal(v, v0)
+
+
+def test_append_paged_lands_in_the_block_the_table_names():
+    lens = [17, 16, 1, 40]
+    p = make_paged("app_p", 52, 4, 8, 2, lens, head_dim=8, page_size=16)
+    rng = np.random.default_rng(2)
+    k_new = f32_to_bf16_bits(rng.standard_normal((4, 2, 8)).astype(np.float32))
+    v_new = f32_to_bf16_bits(rng.standard_normal((4, 2, 8)).astype(np.float32))
+    k0, v0 = p.k.copy(), p.v.copy()
+    kv_append(p.q, k_new, v_new, p.k, p.v, p.kv_lens, block_table=p.block_table, page_size=16)
+    for b, L in enumerate(lens):
+        blk, slot = p.block_table[b, (L - 1) // 16], (L - 1) % 16
+        k0[blk, :, slot] = k_new[b]
+        v0[blk, :, slot] = v_new[b]
+    np.testing.assert_array_equal(p.k, k0)
+    np.testing.assert_array_equal(p.v, v0)
+
+
+def test_rotary_identity_and_quarter_turn():
+    """cos=1, sin=0 leaves q and k unchanged; cos=0, sin=1 maps (x, y) -> (-y, x) for the pair
+    (d, d + D/2): pins the pairing and the sign of the rotation."""
+    D = 8
+    rng = np.random.default_rng(3)
+    q = f32_to_bf16_bits(rng.standard_normal((2, 4, D)).astype(np.float32))
+    k_new = f32_to_bf16_bits(rng.standard_normal((2, 2, D)).astype(np.float32))
+    v_new = f32_to_bf16_bits(rng.standard_normal((2, 2, D)).astype(np.float32))
+    lens = np.array([3, 1])
+    ident = np.zeros((4, D), np.float32); ident[:, :D // 2] = 1.0
+    kc = np.zeros((2, 2, 4, D), np.uint16); vc = kc.copy()
+    np.testing.assert_array_equal(kv_append(q, k_new, v_new, kc, vc, lens, cos_sin=ident), q)
+    np.testing.assert_array_equal(kc[0, :, 2], k_new[0])
+    quarter = np.zeros((4, D), np.float32); quarter[:, D // 2:] = 1.0
+    kc[:] = 0
+    q_out = kv_append(q, k_new, v_new, kc, vc, lens, cos_sin=quarter)
+    qf, of = bf16_bits_to_f32(q), bf16_bits_to_f32(q_out)
+    np.testing.assert_array_equal(of[..., :D // 2], -qf[..., D // 2:])
+    np.testing.assert_array_equal(of[..., D // 2:], qf[..., :D // 2])
+    kf, ko = bf16_bits_to_f32(k_new[1]), bf16_bits_to_f32(kc[1, :, 0])
+    np.testing.assert_array_equal(ko[..., :D // 2], -kf[..., D // 2:])
+    np.testing.assert_array_equal(ko[..., D // 2:], kf[..., :D // 2])
+    np.testing.assert_array_equal(vc[1, :, 0], v_new[1])            # V is never rotated
+
+
+def test_rotary_exact_cases_match_rational_arithmetic():
+    """Small integers and dyadic cos/sin: every result is exactly representable in bf16, so the
+    oracle must return exactly x*c - y*s and y*c + x*s (the table row used is kv_len - 1)."""
+    from fractions import Fraction
+    D = 4
+    rng = np.random.default_rng(4)
+    q = rng.integers(-8, 9, size=(3, 2, D)).astype(np.float32)
+    kn = rng.integers(-8, 9, size=(3, 1, D)).astype(np.float32)
+    table = (rng.integers(-4, 5, size=(6, D)) * 0.25).astype(np.float32)
+    lens = np.array([6, 2, 4])
+    kc = np.zeros((3, 1, 6, D), np.uint16); vc = kc.copy()
+    q_out = bf16_bits_to_f32(kv_append(bits(q), bits(kn), bits(kn), kc, vc, lens, cos_sin=table))
+    for b in range(3):
+        pos = lens[b] - 1
+        for src, got in ((q[b], q_out[b]), (kn[b], bf16_bits_to_f32(kc[b, :, pos]))):
+            for h in range(src.shape[0]):
+                for d in range(D // 2):
+                    c, s = Fraction(float(table[pos, d])), Fraction(float(table[pos, D // 2 + d]))
+                    x, y = Fraction(float(src[h, d])), Fraction(float(src[h, d + D // 2]))
+                    assert Fraction(float(got[h, d])) == x * c - y * s
+                    assert Fraction(float(got[h, d + D // 2])) == y * c + x * s
+
+
+def test_rotary_rounds_to_nearest_even_bf16():
+    D = 2
+    table = np.array([[1.0, 1.0]], np.float32)                     # cos = 1, sin = 1: x' = x - y
+    kc = np.zeros((1, 1, 1, D), np.uint16); vc = kc.copy()
+    cases = [(0x3F80, 2.0 ** -8, 0x3F80),      # 1 + 2^-8: tie between 0x3F80 and 0x3F81 -> even 0x3F80
+             (0x3F81, 2.0 ** -8, 0x3F82),      # 1 + 3*2^-8: tie between 0x3F81 and 0x3F82 -> even 0x3F82
+             (0x3F80, 2.0 ** -9, 0x3F80),      # below the tie
+             (0x3F80, 3 * 2.0 ** -9, 0x3F81)]  # above the tie
+    for xbits, y, want in cases:
+        q = np.array([[[xbits, int(bits(np.float32(-y)))]]], np.uint16)
+        out = kv_append(q, q[:, :1], q[:, :1], kc, vc, np.array([1]), cos_sin=table)
+        assert out[0, 0, 0] == want, (hex(xbits), y, hex(out[0, 0, 0]))
+
+
+def test_rotary_scores_depend_on_relative_position_only():
+    """<R_m q, R_n k> is a function of m - n: shifting both positions changes the dot product only
+    by bf16 rounding.  A rotation in the wrong direction for one of the two breaks this."""
+    D = 64
+    table = rope_table(64, D, theta=100.0)
+    rng = np.random.default_rng(6)
+    q = f32_to_bf16_bits(rng.standard_normal((1, 1, D)).astype(np.float32))
+    kn = f32_to_bf16_bits(rng.standard_normal((1, 1, D)).astype(np.float32))
+    dots = []
+    for shift in (0, 7, 30):
+        kc = np.zeros((1, 1, 64, D), np.uint16); vc = kc.copy()
+        kv_append(q, kn, kn, kc, vc, np.array([5 + shift]), cos_sin=table)       # key at position 4 + shift
+        qr = kv_append(q, kn, kn, kc.copy(), vc, np.array([21 + shift]), cos_sin=table)   # query at 20 + shift
+        dots.append(float(bf16_bits_to_f32(qr[0, 0]).astype(np.float64) @
+                          bf16_bits_to_f32(kc[0, 0, 4 + shift]).astype(np.float64)))
+    scale = float(np.linalg.norm(bf16_bits_to_f32(q)) * np.linalg.norm(bf16_bits_to_f32(kn)))
+    assert max(dots) - min(dots) < 2.0 ** -7 * scale
+    # and the rotation is not the identity: the unrotated dot product differs
+    plain = float(bf16_bits_to_f32(q[0, 0]).astype(np.float64) @ bf16_bits_to_f32(kn[0, 0]).astype(np.float64))
+    assert abs(plain - dots[0]) > 2.0 ** -7 * scale
+
+
+def test_rotary_matches_float64_rotate_half_formula():
+    torch = pytest.importorskip("torch")
+    D = 128
+    table = rope_table(300, D)
+    rng = np.random.default_rng(7)
+    q = f32_to_bf16_bits(rng.standard_normal((4, 6, D)).astype(np.float32))
+    kn = f32_to_bf16_bits(rng.standard_normal((4, 2, D)).astype(np.float32))
+    lens = np.array([300, 1, 77, 150])
+    kc = np.zeros((4, 2, 300, D), np.uint16); vc = kc.copy()
+    got = bf16_bits_to_f32(kv_append(q, kn, kn, kc, vc, lens, cos_sin=table)).astype(np.float64)
+    x = torch.from_numpy(bf16_bits_to_f32(q).astype(np.float64))
+    cos = torch.from_numpy(table[lens - 1, :D // 2].astype(np.float64)).repeat(1, 2)[:, None, :]
+    sin = torch.from_numpy(table[lens - 1, D // 2:].astype(np.float64)).repeat(1, 2)[:, None, :]
+    rot = torch.cat([-x[..., D // 2:], x[..., :D // 2]], dim=-1)
+    want = (x * cos + rot * sin).numpy()
+    # correct rounding to 8 significant bits: every element within half a bf16 step of the exact value
+    assert np.all(np.abs(got - want) <= 2.0 ** -8 * np.abs(want) * (1 + 1e-12))
+    assert np.abs(got - want).max() > 0.0
