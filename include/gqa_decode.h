@@ -172,6 +172,46 @@ int gqa_decode_attn_timed(const gqa_decode_params* params,
                           void* stream, gqa_timer* timer);
 
 /*
+ * The step before attention in a decode layer: append the new token's key and
+ * value rows to the cache and, optionally, apply the rotary position embedding
+ * to the new key and to the query (the 32B model family whose traces the paper
+ * collects, Section 3.3, uses the rotate-half form).
+ *
+ * For every sequence b with L = kv_lens[b] (clamped to max_kv_len) > 0 the new
+ * token sits at position L - 1:
+ *     K[b, L-1, g, :] = rot(k_new[b, g, :]),  V[b, L-1, g, :] = v_new[b, g, :],
+ *     q_out[b, h, :]  = rot(q_in[b, h, :])
+ * with rot the identity if cos_sin is NULL and otherwise, for d < 64,
+ *     x'[d] = x[d] cos[L-1][d] - x[d+64] sin[L-1][d],
+ *     x'[d+64] = x[d+64] cos[L-1][d] + x[d] sin[L-1][d],
+ * evaluated in fp64 and rounded once to bf16 (nearest even).  A sequence with
+ * kv_lens[b] <= 0 gets its query copied unchanged and writes nothing.
+ *
+ *   q_in, q_out  [B, Hq, 128] bf16, both with q_stride_b / q_stride_h; may alias
+ *   k_new, v_new [B, Hkv, 128] bf16, dense
+ *   k_cache, v_cache  as in gqa_decode_attn (contiguous or paged, same strides)
+ *   cos_sin      [rope_positions, 128] fp32: cos in columns [0, 64), sin in
+ *                [64, 128); NULL = no rotation; rope_positions >= max_kv_len
+ * Argument errors as in gqa_decode_attn; nothing is launched on error.
+ */
+typedef struct gqa_append_params {
+    int32_t batch, num_q_heads, num_kv_heads, head_dim;   /* head_dim must be 128 */
+    int32_t max_kv_len;
+    int32_t page_size, block_table_stride;
+    int32_t rope_positions;
+    int64_t q_stride_b, q_stride_h;
+    int64_t k_stride_b, k_stride_h, k_stride_t;
+    int64_t v_stride_b, v_stride_h, v_stride_t;
+} gqa_append_params;
+
+int gqa_decode_kv_append(const gqa_append_params* params,
+                         const void* q_in, void* q_out,
+                         const void* k_new, const void* v_new,
+                         void* k_cache, void* v_cache,
+                         const int32_t* kv_lens, const int32_t* block_table,
+                         const float* cos_sin, void* stream);
+
+/*
  * Streaming-read probe for the HBM roofline: reads `bytes` (a multiple of 16)
  * from `src` with 128-bit loads, folds them into one 32-bit word per
  * workgroup written to `sink` (at least 4*workgroups bytes).  Used by the

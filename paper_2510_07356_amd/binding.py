@@ -25,7 +25,7 @@ GQA_ERR_LAUNCH = -4
 
 EXPORTS = ("gqa_decode_version", "gqa_decode_strerror", "gqa_decode_workspace_bytes",
            "gqa_decode_plan_info", "gqa_decode_attn", "gqa_decode_attn_timed",
-           "gqa_decode_stream_read", "gqa_decode_stream_copy", "gqa_timer_create", "gqa_timer_destroy", "gqa_timer_read")
+           "gqa_decode_kv_append", "gqa_decode_stream_read", "gqa_decode_stream_copy", "gqa_timer_create", "gqa_timer_destroy", "gqa_timer_read")
 
 
 class gqa_decode_params(ctypes.Structure):
@@ -35,6 +35,18 @@ class gqa_decode_params(ctypes.Structure):
         ("max_kv_len", ctypes.c_int32), ("page_size", ctypes.c_int32),
         ("block_table_stride", ctypes.c_int32), ("chunk_tokens", ctypes.c_int32),
         ("scale", ctypes.c_float), ("kernel_variant", ctypes.c_int32),
+        ("q_stride_b", ctypes.c_int64), ("q_stride_h", ctypes.c_int64),
+        ("k_stride_b", ctypes.c_int64), ("k_stride_h", ctypes.c_int64), ("k_stride_t", ctypes.c_int64),
+        ("v_stride_b", ctypes.c_int64), ("v_stride_h", ctypes.c_int64), ("v_stride_t", ctypes.c_int64),
+    ]
+
+
+class gqa_append_params(ctypes.Structure):
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("num_q_heads", ctypes.c_int32),
+        ("num_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+        ("max_kv_len", ctypes.c_int32), ("page_size", ctypes.c_int32),
+        ("block_table_stride", ctypes.c_int32), ("rope_positions", ctypes.c_int32),
         ("q_stride_b", ctypes.c_int64), ("q_stride_h", ctypes.c_int64),
         ("k_stride_b", ctypes.c_int64), ("k_stride_h", ctypes.c_int64), ("k_stride_t", ctypes.c_int64),
         ("v_stride_b", ctypes.c_int64), ("v_stride_h", ctypes.c_int64), ("v_stride_t", ctypes.c_int64),
@@ -74,6 +86,8 @@ def _load() -> ctypes.CDLL:
     lib.gqa_timer_destroy.argtypes = [vp]
     lib.gqa_timer_read.restype = ctypes.c_int
     lib.gqa_timer_read.argtypes = [vp, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_float)]
+    lib.gqa_decode_kv_append.restype = ctypes.c_int
+    lib.gqa_decode_kv_append.argtypes = [ctypes.POINTER(gqa_append_params)] + [vp] * 10
     lib.gqa_decode_stream_read.restype = ctypes.c_int
     lib.gqa_decode_stream_read.argtypes = [vp, ctypes.c_size_t, vp, ctypes.c_int32, vp]
     lib.gqa_decode_stream_copy.restype = ctypes.c_int
@@ -234,6 +248,39 @@ def gqa_decode_attn(params: gqa_decode_params, q: torch.Tensor, k: torch.Tensor,
     if rc != GQA_OK:
         raise GqaError(rc)
     return None
+
+
+def gqa_decode_kv_append(q_in: torch.Tensor, q_out: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor,
+                         k_cache: torch.Tensor, v_cache: torch.Tensor, kv_lens: torch.Tensor, max_kv_len: int,
+                         block_table: Optional[torch.Tensor] = None, page_size: int = 0,
+                         cos_sin: Optional[torch.Tensor] = None,
+                         stream: Optional[torch.cuda.Stream] = None) -> None:
+    """q_in/q_out [B, Hq, D] (same strides); k_new, v_new [B, Hkv, D] dense; caches indexed
+    [b | block, kv head, token | slot, d]; cos_sin [positions, D] fp32 or None."""
+    for t in (q_in, q_out, k_new, v_new, k_cache, v_cache):
+        if not t.is_cuda or t.dtype != torch.bfloat16 or t.stride(-1) != 1:
+            raise TypeError("bf16 device tensors with a dense last axis expected")
+    if q_in.stride() != q_out.stride() or not k_new.is_contiguous() or not v_new.is_contiguous():
+        raise ValueError("q_in/q_out must share strides; k_new/v_new must be dense")
+    if cos_sin is not None and (cos_sin.dtype != torch.float32 or not cos_sin.is_contiguous() or not cos_sin.is_cuda):
+        raise TypeError("cos_sin must be a dense fp32 device tensor")
+    p = gqa_append_params()
+    p.batch, p.num_q_heads, p.head_dim = q_in.shape
+    p.num_kv_heads = k_new.shape[1]
+    p.max_kv_len = int(max_kv_len)
+    p.page_size = int(page_size)
+    p.block_table_stride = int(block_table.stride(0)) if block_table is not None else 0
+    p.rope_positions = int(cos_sin.shape[0]) if cos_sin is not None else 0
+    p.q_stride_b, p.q_stride_h = q_in.stride(0), q_in.stride(1)
+    p.k_stride_b, p.k_stride_h, p.k_stride_t = k_cache.stride(0), k_cache.stride(1), k_cache.stride(2)
+    p.v_stride_b, p.v_stride_h, p.v_stride_t = v_cache.stride(0), v_cache.stride(1), v_cache.stride(2)
+    s = stream if stream is not None else torch.cuda.current_stream(q_in.device)
+    rc = _lib.gqa_decode_kv_append(ctypes.byref(p), q_in.data_ptr(), q_out.data_ptr(), k_new.data_ptr(),
+                                   v_new.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(), kv_lens.data_ptr(),
+                                   block_table.data_ptr() if block_table is not None else None,
+                                   cos_sin.data_ptr() if cos_sin is not None else None, s.cuda_stream)
+    if rc != GQA_OK:
+        raise GqaError(rc)
 
 
 def gqa_decode_stream_read(src: torch.Tensor, sink: torch.Tensor, workgroups: int,

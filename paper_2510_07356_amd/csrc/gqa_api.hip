@@ -278,6 +278,41 @@ int gqa_timer_read(gqa_timer* timer, int32_t* host_calls, float host_kernel_ms[2
     return status;
 }
 
+int gqa_decode_kv_append(const gqa_append_params* p, const void* q_in, void* q_out, const void* k_new,
+                         const void* v_new, void* k_cache, void* v_cache, const int32_t* kv_lens,
+                         const int32_t* block_table, const float* cos_sin, void* stream) {
+    if (p == nullptr) return GQA_ERR_INVALID_ARG;
+    if (p->batch < 1 || p->num_q_heads < 1 || p->num_kv_heads < 1 || p->max_kv_len < 0 || p->page_size < 0)
+        return GQA_ERR_INVALID_ARG;
+    if (p->head_dim != gqa::kHeadDim) return GQA_ERR_UNSUPPORTED;
+    if (p->page_size != 0) {
+        if (p->page_size < 16 || (p->page_size & (p->page_size - 1)) != 0) return GQA_ERR_UNSUPPORTED;
+        if ((int64_t)p->block_table_stride * p->page_size < p->max_kv_len) return GQA_ERR_INVALID_ARG;
+    }
+    if (!q_in || !q_out || !k_new || !v_new || !k_cache || !v_cache || !kv_lens) return GQA_ERR_INVALID_ARG;
+    if ((p->page_size != 0) != (block_table != nullptr)) return GQA_ERR_INVALID_ARG;
+    if (cos_sin != nullptr && p->rope_positions < p->max_kv_len) return GQA_ERR_INVALID_ARG;
+    if (p->k_stride_t < gqa::kHeadDim || p->v_stride_t < gqa::kHeadDim || p->q_stride_h < gqa::kHeadDim)
+        return GQA_ERR_INVALID_ARG;
+    gqa::AppendArgs a{};
+    a.q_in = static_cast<const uint16_t*>(q_in);
+    a.q_out = static_cast<uint16_t*>(q_out);
+    a.k_new = static_cast<const uint16_t*>(k_new);
+    a.v_new = static_cast<const uint16_t*>(v_new);
+    a.k_cache = static_cast<uint16_t*>(k_cache);
+    a.v_cache = static_cast<uint16_t*>(v_cache);
+    a.kv_lens = kv_lens;
+    a.block_table = block_table;
+    a.cos_sin = cos_sin;
+    a.batch = p->batch; a.num_q_heads = p->num_q_heads; a.num_kv_heads = p->num_kv_heads;
+    a.max_kv_len = p->max_kv_len;
+    a.page_size = p->page_size; a.block_table_stride = p->block_table_stride;
+    a.q_stride_b = p->q_stride_b; a.q_stride_h = p->q_stride_h;
+    a.k_stride_b = p->k_stride_b; a.k_stride_h = p->k_stride_h; a.k_stride_t = p->k_stride_t;
+    a.v_stride_b = p->v_stride_b; a.v_stride_h = p->v_stride_h; a.v_stride_t = p->v_stride_t;
+    return gqa::launch_kv_append(a, static_cast<hipStream_t>(stream)) == hipSuccess ? GQA_OK : GQA_ERR_LAUNCH;
+}
+
 int gqa_decode_stream_read(const void* src, size_t bytes, void* sink, int32_t workgroups, void* stream) {
     if (!src || !sink || workgroups < 1 || bytes % 16 != 0 || !aligned16(src)) return GQA_ERR_INVALID_ARG;
     return gqa::launch_stream_read(src, bytes, sink, workgroups, static_cast<hipStream_t>(stream)) == hipSuccess

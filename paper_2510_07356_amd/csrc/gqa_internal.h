@@ -185,6 +185,25 @@ __device__ __forceinline__ StreamPos wave_stream_locate(const KernelArgs& a, int
     return p;
 }
 
+// Device-side view of one append call.
+struct AppendArgs {
+    const uint16_t* q_in;
+    uint16_t* q_out;
+    const uint16_t* k_new;   // [batch, Hkv, D] dense
+    const uint16_t* v_new;
+    uint16_t* k_cache;
+    uint16_t* v_cache;
+    const int32_t* kv_lens;
+    const int32_t* block_table;
+    const float* cos_sin;    // [positions, D]: cos in columns [0, D/2), sin in [D/2, D); may be null
+    int32_t batch, num_q_heads, num_kv_heads, max_kv_len;
+    int32_t page_size, block_table_stride;
+    int64_t q_stride_b, q_stride_h;
+    int64_t k_stride_b, k_stride_h, k_stride_t;
+    int64_t v_stride_b, v_stride_h, v_stride_t;
+};
+hipError_t launch_kv_append(const AppendArgs& a, hipStream_t s);
+
 // Launchers (each checks nothing: the C-ABI layer validated the arguments).
 hipError_t launch_partial_valu(const KernelArgs& a, int workgroups, hipStream_t s);
 hipError_t launch_partial_mfma(const KernelArgs& a, int workgroups, hipStream_t s);

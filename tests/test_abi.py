@@ -101,3 +101,27 @@ def test_bad_pointers_and_workspace_are_rejected_before_launch(lib):
     assert call(pp=params(lib, k_stride_t=132)) == -1           # rows not 16-byte aligned
     assert call(pp=params(lib, page_size=16, block_table_stride=256)) == -1   # paging without table
     assert raw.gqa_decode_attn(None, good, good, good, good, None, None, good, None, good, need, None) == -1
+
+
+def test_append_rejects_bad_arguments_before_launch(lib):
+    raw = lib._lib
+    p = lib.gqa_append_params()
+    p.batch, p.num_q_heads, p.num_kv_heads, p.head_dim = 2, 40, 8, 128
+    p.max_kv_len, p.page_size, p.block_table_stride, p.rope_positions = 512, 0, 0, 512
+    p.q_stride_b, p.q_stride_h = 40 * 128, 128
+    p.k_stride_b, p.k_stride_h, p.k_stride_t = 8 * 512 * 128, 512 * 128, 128
+    p.v_stride_b, p.v_stride_h, p.v_stride_t = 8 * 512 * 128, 512 * 128, 128
+    g = 0x10000
+    def call(pp=p, q=g, cs=g, bt=None):
+        return raw.gqa_decode_kv_append(ctypes.byref(pp), q, g, g, g, g, g, g, bt, cs, None)
+    assert call(q=None) == -1
+    assert call(bt=g) == -1                                  # block table without paging
+    p.rope_positions = 100
+    assert call() == -1                                      # table shorter than the length bound
+    p.rope_positions = 512
+    p.head_dim = 64
+    assert call() == -2
+    p.head_dim = 128
+    p.page_size = 24
+    assert call() == -2
+    assert raw.gqa_decode_kv_append(None, g, g, g, g, g, g, g, None, None, None) == -1
