@@ -172,6 +172,52 @@ int gqa_decode_attn_timed(const gqa_decode_params* params,
                           void* stream, gqa_timer* timer);
 
 /*
+ * Shared-prefix ("cascade") decode attention.  The paper's workload samples
+ * every prompt several times (5 generations per task when the data are
+ * collected, Section 3.3; 10 per task at evaluation, Section 4.2), so the
+ * sequences of a batch come in groups that share the prompt's keys and values.
+ * Here the shared prefix of a group is stored once and read once per KV head
+ * for all samples of the group; each sequence attends over
+ *     [ prefix of its group (prefix_lens[j] tokens) ; its own suffix (kv_lens[b] tokens) ]
+ * and the result is exactly the attention defined at the top of this header
+ * over that concatenation.
+ *
+ *   params->decode  shapes of q and of the per-sequence SUFFIX caches (contiguous
+ *                   or paged, as in gqa_decode_attn); max_kv_len bounds kv_lens
+ *   k_prefix, v_prefix  bf16, row (j, g, t) at  j*kp_stride_g + g*kp_stride_h + t*kp_stride_t
+ *   prefix_lens     [num_groups] int32 (device), clamped to [0, max_prefix_len]
+ *   group_start     [num_groups + 1] int32 (device): group j holds sequences
+ *                   group_start[j] .. group_start[j+1]-1; group_start[0] = 0,
+ *                   group_start[num_groups] = batch, non-decreasing
+ *   host_group_start  the same array in HOST memory (required): the library checks
+ *                   it before launching.  A group may hold at most
+ *                   64 / (num_q_heads / num_kv_heads) sequences (GQA_ERR_UNSUPPORTED beyond)
+ *   kv_lens, block_table, out, lse, workspace, stream  as in gqa_decode_attn;
+ *                   workspace >= gqa_cascade_workspace_bytes(params)
+ * Only the matrix-core kernel exists for this entry point (kernel_variant must be 0).
+ */
+typedef struct gqa_cascade_params {
+    gqa_decode_params decode;
+    int32_t num_groups;          /* >= 1                                   */
+    int32_t max_prefix_len;      /* host-known bound of prefix_lens[]      */
+    int64_t kp_stride_g, kp_stride_h, kp_stride_t;
+    int64_t vp_stride_g, vp_stride_h, vp_stride_t;
+} gqa_cascade_params;
+
+size_t gqa_cascade_workspace_bytes(const gqa_cascade_params* params);
+
+int gqa_decode_attn_shared_prefix(const gqa_cascade_params* params,
+                                  const void* q,
+                                  const void* k_prefix, const void* v_prefix,
+                                  const int32_t* prefix_lens, const int32_t* group_start,
+                                  const int32_t* host_group_start,
+                                  const void* k, const void* v,
+                                  const int32_t* kv_lens, const int32_t* block_table,
+                                  float* out, float* lse,
+                                  void* workspace, size_t workspace_bytes,
+                                  void* stream);
+
+/*
  * The step before attention in a decode layer: append the new token's key and
  * value rows to the cache and, optionally, apply the rotary position embedding
  * to the new key and to the query (the 32B model family whose traces the paper

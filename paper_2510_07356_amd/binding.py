@@ -25,7 +25,7 @@ GQA_ERR_LAUNCH = -4
 
 EXPORTS = ("gqa_decode_version", "gqa_decode_strerror", "gqa_decode_workspace_bytes",
            "gqa_decode_plan_info", "gqa_decode_attn", "gqa_decode_attn_timed",
-           "gqa_decode_kv_append", "gqa_decode_stream_read", "gqa_decode_stream_copy", "gqa_timer_create", "gqa_timer_destroy", "gqa_timer_read")
+           "gqa_decode_kv_append", "gqa_cascade_workspace_bytes", "gqa_decode_attn_shared_prefix", "gqa_decode_stream_read", "gqa_decode_stream_copy", "gqa_timer_create", "gqa_timer_destroy", "gqa_timer_read")
 
 
 class gqa_decode_params(ctypes.Structure):
@@ -50,6 +50,15 @@ class gqa_append_params(ctypes.Structure):
         ("q_stride_b", ctypes.c_int64), ("q_stride_h", ctypes.c_int64),
         ("k_stride_b", ctypes.c_int64), ("k_stride_h", ctypes.c_int64), ("k_stride_t", ctypes.c_int64),
         ("v_stride_b", ctypes.c_int64), ("v_stride_h", ctypes.c_int64), ("v_stride_t", ctypes.c_int64),
+    ]
+
+
+class gqa_cascade_params(ctypes.Structure):
+    _fields_ = [
+        ("decode", gqa_decode_params),
+        ("num_groups", ctypes.c_int32), ("max_prefix_len", ctypes.c_int32),
+        ("kp_stride_g", ctypes.c_int64), ("kp_stride_h", ctypes.c_int64), ("kp_stride_t", ctypes.c_int64),
+        ("vp_stride_g", ctypes.c_int64), ("vp_stride_h", ctypes.c_int64), ("vp_stride_t", ctypes.c_int64),
     ]
 
 
@@ -86,6 +95,10 @@ def _load() -> ctypes.CDLL:
     lib.gqa_timer_destroy.argtypes = [vp]
     lib.gqa_timer_read.restype = ctypes.c_int
     lib.gqa_timer_read.argtypes = [vp, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_float)]
+    lib.gqa_cascade_workspace_bytes.restype = ctypes.c_size_t
+    lib.gqa_cascade_workspace_bytes.argtypes = [ctypes.POINTER(gqa_cascade_params)]
+    lib.gqa_decode_attn_shared_prefix.restype = ctypes.c_int
+    lib.gqa_decode_attn_shared_prefix.argtypes = [ctypes.POINTER(gqa_cascade_params)] + [vp] * 13 + [ctypes.c_size_t, vp]
     lib.gqa_decode_kv_append.restype = ctypes.c_int
     lib.gqa_decode_kv_append.argtypes = [ctypes.POINTER(gqa_append_params)] + [vp] * 10
     lib.gqa_decode_stream_read.restype = ctypes.c_int
@@ -248,6 +261,74 @@ def gqa_decode_attn(params: gqa_decode_params, q: torch.Tensor, k: torch.Tensor,
     if rc != GQA_OK:
         raise GqaError(rc)
     return None
+
+
+def gqa_cascade_workspace_bytes(params: gqa_cascade_params) -> int:
+    return int(_lib.gqa_cascade_workspace_bytes(ctypes.byref(params)))
+
+
+def make_cascade_params(q, k, v, kp, vp, max_kv_len, max_prefix_len, num_groups, scale, page_size=0,
+                        block_table=None, chunk_tokens=0) -> gqa_cascade_params:
+    cp = gqa_cascade_params()
+    cp.decode = make_params(q, k, v, max_kv_len, scale, page_size, block_table, chunk_tokens, 0)
+    cp.num_groups, cp.max_prefix_len = int(num_groups), int(max_prefix_len)
+    cp.kp_stride_g, cp.kp_stride_h, cp.kp_stride_t = kp.stride(0), kp.stride(1), kp.stride(2)
+    cp.vp_stride_g, cp.vp_stride_h, cp.vp_stride_t = vp.stride(0), vp.stride(1), vp.stride(2)
+    return cp
+
+
+class CascadeCall:
+    """Pre-marshalled gqa_decode_attn_shared_prefix call."""
+
+    def __init__(self, cp, q, kp, vp, prefix_lens, group_start, host_group_start, k, v, kv_lens, block_table,
+                 out, lse, workspace, stream: Optional[torch.cuda.Stream] = None):
+        _check_inputs(q, k, v, kv_lens, block_table, out, lse, workspace)
+        for t in (kp, vp):
+            if not t.is_cuda or t.dtype != torch.bfloat16 or t.stride(-1) != 1:
+                raise TypeError("prefix caches must be bf16 device tensors with a dense last axis")
+        for t in (prefix_lens, group_start):
+            if not t.is_cuda or t.dtype != torch.int32 or not t.is_contiguous():
+                raise TypeError("prefix_lens / group_start must be dense int32 device tensors")
+        hptr, self._keep = _host_lens_ptr(host_group_start)
+        s = stream if stream is not None else torch.cuda.current_stream(q.device)
+        self._tensors = (cp, q, kp, vp, prefix_lens, group_start, k, v, kv_lens, block_table, out, lse, workspace)
+        self.args = [ctypes.byref(cp), q.data_ptr(), kp.data_ptr(), vp.data_ptr(), prefix_lens.data_ptr(),
+                     group_start.data_ptr(), hptr, k.data_ptr(), v.data_ptr(), kv_lens.data_ptr(),
+                     block_table.data_ptr() if block_table is not None else None,
+                     out.data_ptr(), lse.data_ptr() if lse is not None else None,
+                     workspace.data_ptr(), workspace.numel(), s.cuda_stream]
+
+    def __call__(self) -> None:
+        rc = _lib.gqa_decode_attn_shared_prefix(*self.args)
+        if rc != GQA_OK:
+            raise GqaError(rc)
+
+
+def shared_prefix_to_device(sw, device="cuda:0"):
+    dev = to_device(sw.base, device)
+    dev["kp"] = _bf16_view(sw.kp).to(device)
+    dev["vp"] = _bf16_view(sw.vp).to(device)
+    dev["prefix_lens"] = torch.from_numpy(sw.prefix_lens).to(device)
+    dev["group_start"] = torch.from_numpy(sw.group_start).to(device)
+    return dev
+
+
+def run_shared_prefix(sw, dev=None, chunk_tokens: int = 0, want_lse: bool = True):
+    """One gqa_decode_attn_shared_prefix call on a workloads.SharedPrefixWorkload; returns (out, lse)."""
+    w = sw.base
+    dev = dev if dev is not None else shared_prefix_to_device(sw)
+    cp = make_cascade_params(dev["q"], dev["k"], dev["v"], dev["kp"], dev["vp"], w.max_kv_len,
+                             int(sw.prefix_lens.max(initial=0)), len(sw.prefix_lens), w.scale, w.page_size,
+                             dev["block_table"], chunk_tokens)
+    nbytes = gqa_cascade_workspace_bytes(cp)
+    if nbytes == 0:
+        raise GqaError(GQA_ERR_UNSUPPORTED)
+    ws = torch.full((nbytes,), 0xFF, dtype=torch.uint8, device=dev["q"].device)
+    out = torch.full((w.batch, w.num_q_heads, w.head_dim), float("nan"), dtype=torch.float32, device=dev["q"].device)
+    lse = torch.full((w.batch, w.num_q_heads), float("nan"), dtype=torch.float32, device=dev["q"].device) if want_lse else None
+    CascadeCall(cp, dev["q"], dev["kp"], dev["vp"], dev["prefix_lens"], dev["group_start"], sw.group_start,
+                dev["k"], dev["v"], dev["kv_lens"], dev["block_table"], out, lse, ws)()
+    return out, lse
 
 
 def gqa_decode_kv_append(q_in: torch.Tensor, q_out: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor,

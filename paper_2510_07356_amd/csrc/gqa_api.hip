@@ -278,6 +278,128 @@ int gqa_timer_read(gqa_timer* timer, int32_t* host_calls, float host_kernel_ms[2
     return status;
 }
 
+namespace {
+
+struct CascadePlan {
+    int64_t slots;
+    size_t header_bytes, prefix_bytes, ml_bytes, o_bytes;
+    size_t total_bytes() const { return header_bytes + prefix_bytes + ml_bytes + o_bytes; }
+};
+
+int make_cascade_plan(const gqa_cascade_params* cp, CascadePlan* plan) {
+    if (cp == nullptr) return GQA_ERR_INVALID_ARG;
+    const gqa_decode_params* p = &cp->decode;
+    const int rc = check_shape(p);
+    if (rc != GQA_OK) return rc;
+    if (p->kernel_variant != 0) return GQA_ERR_UNSUPPORTED;
+    if (cp->num_groups < 1 || cp->num_groups > p->batch || cp->max_prefix_len < 0) return GQA_ERR_INVALID_ARG;
+    const int64_t entries = (int64_t)cp->num_groups + p->batch;
+    const int64_t max_tiles = (int64_t)p->num_kv_heads *
+        ((int64_t)cp->num_groups * gqa::tiles_of(cp->max_prefix_len) + (int64_t)p->batch * gqa::tiles_of(p->max_kv_len));
+    if (max_tiles > 0x3fffffffLL) return GQA_ERR_UNSUPPORTED;
+    int64_t shares = kMaxWorkers;
+    const int fixed = p->chunk_tokens / gqa::kTileTokens;
+    if (fixed > 0 && (max_tiles + fixed - 1) / fixed > shares) shares = (max_tiles + fixed - 1) / fixed;
+    plan->slots = shares + entries * p->num_kv_heads;
+    plan->header_bytes = 256;
+    plan->prefix_bytes = align_up(sizeof(int32_t) * ((size_t)entries + 1), 256);
+    plan->ml_bytes = align_up((size_t)plan->slots * gqa::kCascadeColumns * 2 * sizeof(float), 256);
+    plan->o_bytes = align_up((size_t)plan->slots * gqa::kCascadeColumns * gqa::kHeadDim * sizeof(float), 256);
+    return GQA_OK;
+}
+
+}  // namespace
+
+size_t gqa_cascade_workspace_bytes(const gqa_cascade_params* params) {
+    CascadePlan plan;
+    if (make_cascade_plan(params, &plan) != GQA_OK) return 0;
+    return plan.total_bytes();
+}
+
+int gqa_decode_attn_shared_prefix(const gqa_cascade_params* cp, const void* q, const void* k_prefix,
+                                  const void* v_prefix, const int32_t* prefix_lens, const int32_t* group_start,
+                                  const int32_t* host_group_start, const void* k, const void* v,
+                                  const int32_t* kv_lens, const int32_t* block_table, float* out, float* lse,
+                                  void* workspace, size_t workspace_bytes, void* stream) {
+    CascadePlan plan;
+    const int rc = make_cascade_plan(cp, &plan);
+    if (rc != GQA_OK) return rc;
+    const gqa_decode_params* p = &cp->decode;
+    if (!q || !k_prefix || !v_prefix || !prefix_lens || !group_start || !host_group_start || !k || !v ||
+        !kv_lens || !out || !workspace)
+        return GQA_ERR_INVALID_ARG;
+    if ((p->page_size != 0) != (block_table != nullptr)) return GQA_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(k_prefix) || !aligned16(v_prefix) ||
+        !aligned16(out))
+        return GQA_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return GQA_ERR_INVALID_ARG;
+    if (!mult8(p->q_stride_b) || !mult8(p->q_stride_h) || !mult8(p->k_stride_b) || !mult8(p->k_stride_h) ||
+        !mult8(p->k_stride_t) || !mult8(p->v_stride_b) || !mult8(p->v_stride_h) || !mult8(p->v_stride_t) ||
+        !mult8(cp->kp_stride_g) || !mult8(cp->kp_stride_h) || !mult8(cp->kp_stride_t) ||
+        !mult8(cp->vp_stride_g) || !mult8(cp->vp_stride_h) || !mult8(cp->vp_stride_t))
+        return GQA_ERR_INVALID_ARG;
+    if (p->k_stride_t < gqa::kHeadDim || p->v_stride_t < gqa::kHeadDim || p->q_stride_h < gqa::kHeadDim ||
+        cp->kp_stride_t < gqa::kHeadDim || cp->vp_stride_t < gqa::kHeadDim)
+        return GQA_ERR_INVALID_ARG;
+    const int group = p->num_q_heads / p->num_kv_heads;
+    if (host_group_start[0] != 0 || host_group_start[cp->num_groups] != p->batch) return GQA_ERR_INVALID_ARG;
+    for (int j = 0; j < cp->num_groups; ++j) {
+        const int64_t m = (int64_t)host_group_start[j + 1] - host_group_start[j];
+        if (m < 0) return GQA_ERR_INVALID_ARG;
+        if (m * group > gqa::kCascadeColumns) return GQA_ERR_UNSUPPORTED;
+    }
+    if (workspace_bytes < plan.total_bytes()) return GQA_ERR_WORKSPACE_TOO_SMALL;
+
+    gqa::CascadeArgs ca{};
+    KernelArgs& a = ca.base;
+    a.q = static_cast<const uint16_t*>(q);
+    a.k = static_cast<const uint16_t*>(k);
+    a.v = static_cast<const uint16_t*>(v);
+    a.kv_lens = kv_lens;
+    a.block_table = block_table;
+    char* ws = static_cast<char*>(workspace);
+    a.header = reinterpret_cast<int32_t*>(ws);
+    a.row_prefix = reinterpret_cast<int32_t*>(ws + plan.header_bytes);
+    a.part_ml = reinterpret_cast<float*>(ws + plan.header_bytes + plan.prefix_bytes);
+    a.part_o = reinterpret_cast<float*>(ws + plan.header_bytes + plan.prefix_bytes + plan.ml_bytes);
+    a.out = out;
+    a.lse = lse;
+    a.batch = p->batch;
+    a.num_q_heads = p->num_q_heads;
+    a.num_kv_heads = p->num_kv_heads;
+    a.group = group;
+    a.max_kv_len = p->max_kv_len;
+    a.fixed_share_tiles = p->chunk_tokens / gqa::kTileTokens;
+    a.page_size = p->page_size;
+    a.page_shift = 0;
+    while (p->page_size > 1 && (1 << a.page_shift) < p->page_size) ++a.page_shift;
+    a.block_table_stride = p->block_table_stride;
+    a.q_stride_b = p->q_stride_b; a.q_stride_h = p->q_stride_h;
+    a.k_stride_b = p->k_stride_b; a.k_stride_h = p->k_stride_h; a.k_stride_t = p->k_stride_t;
+    a.v_stride_b = p->v_stride_b; a.v_stride_h = p->v_stride_h; a.v_stride_t = p->v_stride_t;
+    a.scale_log2e = p->scale * 1.4426950408889634f;
+    ca.kp = static_cast<const uint16_t*>(k_prefix);
+    ca.vp = static_cast<const uint16_t*>(v_prefix);
+    ca.prefix_lens = prefix_lens;
+    ca.group_start = group_start;
+    ca.num_groups = cp->num_groups;
+    ca.max_prefix_len = cp->max_prefix_len;
+    ca.kp_stride_g = cp->kp_stride_g; ca.kp_stride_h = cp->kp_stride_h; ca.kp_stride_t = cp->kp_stride_t;
+    ca.vp_stride_g = cp->vp_stride_g; ca.vp_stride_h = cp->vp_stride_h; ca.vp_stride_t = cp->vp_stride_t;
+
+    int workgroups = workgroups_for(0);
+    if (workgroups < 1) return GQA_ERR_LAUNCH;
+    const int per_group = gqa::partial_cascade_workers_per_group();
+    const int64_t max_tiles = (int64_t)p->num_kv_heads *
+        ((int64_t)cp->num_groups * gqa::tiles_of(cp->max_prefix_len) + (int64_t)p->batch * gqa::tiles_of(p->max_kv_len));
+    const int64_t useful = (max_tiles + gqa::kMinShareTiles * per_group - 1) / (gqa::kMinShareTiles * per_group);
+    if (useful < workgroups) workgroups = (int)(useful > 0 ? useful : 1);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (gqa::launch_partial_cascade(ca, workgroups, s) != hipSuccess) return GQA_ERR_LAUNCH;
+    if (gqa::launch_combine_cascade(ca, s) != hipSuccess) return GQA_ERR_LAUNCH;
+    return GQA_OK;
+}
+
 int gqa_decode_kv_append(const gqa_append_params* p, const void* q_in, void* q_out, const void* k_new,
                          const void* v_new, void* k_cache, void* v_cache, const int32_t* kv_lens,
                          const int32_t* block_table, const float* cos_sin, void* stream) {

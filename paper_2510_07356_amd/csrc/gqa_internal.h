@@ -185,6 +185,25 @@ __device__ __forceinline__ StreamPos wave_stream_locate(const KernelArgs& a, int
     return p;
 }
 
+// Device-side view of one shared-prefix ("cascade") call: `base` describes the queries, the
+// per-sequence suffix caches (kv_lens = suffix lengths) and the outputs; the prefix of group j
+// lives at kp + j*kp_stride_g + g*kp_stride_h + t*kp_stride_t.  base.row_prefix holds one stream
+// position per entry (num_groups prefixes, then batch suffixes) plus the total.
+constexpr int kCascadeColumns = 64;      // query rows (samples x heads of a KV group) one prefix row can serve
+struct CascadeArgs {
+    KernelArgs base;
+    const uint16_t* kp;
+    const uint16_t* vp;
+    const int32_t* prefix_lens;      // [num_groups]
+    const int32_t* group_start;      // [num_groups + 1], sequences of group j: [group_start[j], group_start[j+1])
+    int32_t num_groups, max_prefix_len;
+    int64_t kp_stride_g, kp_stride_h, kp_stride_t;
+    int64_t vp_stride_g, vp_stride_h, vp_stride_t;
+};
+hipError_t launch_partial_cascade(const CascadeArgs& ca, int workgroups, hipStream_t s);
+hipError_t launch_combine_cascade(const CascadeArgs& ca, hipStream_t s);
+int partial_cascade_workers_per_group();
+
 // Device-side view of one append call.
 struct AppendArgs {
     const uint16_t* q_in;

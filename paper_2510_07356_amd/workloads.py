@@ -224,3 +224,97 @@ def make_config(index: int, layout: str = "head_major") -> Workload:
         return make_paged(CONFIG_NAMES[4], 4, 128, 32, 8, lens, table_width=32768 // PAGE,
                           layout=layout)
     raise IndexError(index)
+
+
+# ---------------------------------------------------------------------------
+# Shared-prefix batches: the samples drawn for one prompt share the prompt's K/V
+# ---------------------------------------------------------------------------
+
+@dataclass
+class SharedPrefixWorkload:
+    """`base` holds the queries and the per-sequence SUFFIX caches (kv_lens = suffix lengths);
+    the prefix of group j is kp[j, :, :prefix_lens[j]] / vp[...], stored once per group."""
+    base: Workload
+    kp: np.ndarray                 # [groups, Hkv, Pmax, D] uint16
+    vp: np.ndarray
+    prefix_lens: np.ndarray        # [groups] int32
+    group_start: np.ndarray        # [groups + 1] int32
+
+    @property
+    def logical_kv_bytes(self) -> int:
+        """K+V bytes an implementation without sharing would read (every sequence its own prefix copy)."""
+        m = np.diff(self.group_start).astype(np.int64)
+        tokens = int((m * self.prefix_lens.astype(np.int64)).sum()) + self.base.kv_tokens
+        return tokens * 2 * self.base.num_kv_heads * self.base.head_dim * 2
+
+    @property
+    def physical_kv_bytes(self) -> int:
+        """K+V bytes that exist in memory: each prefix once, plus the suffixes."""
+        tokens = int(self.prefix_lens.astype(np.int64)[np.diff(self.group_start) > 0].sum()) + self.base.kv_tokens
+        return tokens * 2 * self.base.num_kv_heads * self.base.head_dim * 2
+
+    def concatenated(self) -> Workload:
+        """The same attention problem without sharing: one contiguous cache per sequence holding
+        [prefix of its group ; its suffix].  This is what the oracle is given."""
+        w = self.base
+        B, Hkv, D = w.batch, w.num_kv_heads, w.head_dim
+        group_of = np.repeat(np.arange(len(self.prefix_lens)), np.diff(self.group_start))
+        full = self.prefix_lens[group_of].astype(np.int64) + w.kv_lens.astype(np.int64)
+        lmax = max(int(full.max(initial=0)), 1)
+        k = np.full((B, Hkv, lmax, D), BF16_POISON, dtype=np.uint16)
+        v = np.full((B, Hkv, lmax, D), BF16_POISON, dtype=np.uint16)
+        for b in range(B):
+            j, P, S = int(group_of[b]), int(self.prefix_lens[group_of[b]]), int(w.kv_lens[b])
+            k[b, :, :P] = self.kp[j, :, :P]
+            v[b, :, :P] = self.vp[j, :, :P]
+            for t in range(S):
+                if w.page_size:
+                    blk, slot = int(w.block_table[b, t // w.page_size]), t % w.page_size
+                    k[b, :, P + t] = w.k[blk, :, slot]
+                    v[b, :, P + t] = w.v[blk, :, slot]
+                else:
+                    break
+            if not w.page_size:
+                k[b, :, P:P + S] = w.k[b, :, :S]
+                v[b, :, P:P + S] = w.v[b, :, :S]
+        return Workload(w.name + "_concat", B, w.num_q_heads, Hkv, D, w.scale, 0, w.q, k, v,
+                        full.astype(np.int32), None, "head_major")
+
+
+def make_shared_prefix(name: str, seed: int, group_sizes: Sequence[int], prefix_lens: Sequence[int],
+                       suffix_lens: Sequence[int], num_q_heads: int = 40, num_kv_heads: int = 8,
+                       head_dim: int = 128, paged: bool = False, layout: str = "head_major",
+                       prefix_cache_len: Optional[int] = None, **kw) -> SharedPrefixWorkload:
+    group_sizes = np.asarray(group_sizes, dtype=np.int32)
+    prefix_lens = np.asarray(prefix_lens, dtype=np.int32)
+    batch = int(group_sizes.sum())
+    assert len(prefix_lens) == len(group_sizes) and len(suffix_lens) == batch
+    if paged:
+        base = make_paged(name, seed, batch, num_q_heads, num_kv_heads, suffix_lens, head_dim=head_dim,
+                          layout=layout, **kw)
+    else:
+        base = make_contiguous(name, seed, batch, num_q_heads, num_kv_heads, suffix_lens, head_dim=head_dim,
+                               layout=layout, **kw)
+    pmax = int(prefix_cache_len if prefix_cache_len is not None else max(int(prefix_lens.max(initial=0)), 1))
+    kp = np.full((len(group_sizes), num_kv_heads, pmax, head_dim), BF16_POISON, dtype=np.uint16)
+    vp = np.full_like(kp, BF16_POISON)
+    for j, P in enumerate(prefix_lens):
+        if P > 0:
+            kp[j, :, :P] = _normal_bits(seed + 1000, _STREAM_K, j, (num_kv_heads, int(P), head_dim))
+            vp[j, :, :P] = _normal_bits(seed + 1000, _STREAM_V, j, (num_kv_heads, int(P), head_dim))
+    start = np.concatenate([[0], np.cumsum(group_sizes)]).astype(np.int32)
+    return SharedPrefixWorkload(base, kp, vp, prefix_lens, start)
+
+
+def make_sampling_batch(seed: int = 5, tasks: int = 12, samples: int = 5, prompt_median: float = 1800.0,
+                        trace_median: float = 6000.0, sigma: float = 0.6, cap: int = 32768) -> SharedPrefixWorkload:
+    """A decode batch shaped like the paper's trace synthesis: `tasks` prompts, `samples` traces
+    per prompt (Section 3.3 draws 5 per task), prompt lengths lognormal around `prompt_median`
+    tokens, generated-so-far lengths lognormal around `trace_median` (Table 3: 6-7 thousand
+    tokens on average), total length capped at `cap` (Section 4.1)."""
+    rng = _rng(seed, _STREAM_LENS)
+    prompts = np.clip(np.rint(np.exp(math.log(prompt_median) + 0.3 * rng.standard_normal(tasks))), 16, cap // 4)
+    traces = np.clip(np.rint(np.exp(math.log(trace_median) + sigma * rng.standard_normal(tasks * samples))), 1, None)
+    traces = np.minimum(traces, cap - np.repeat(prompts, samples))
+    return make_shared_prefix(f"sampling_{tasks}x{samples}", seed, [samples] * tasks, prompts.astype(np.int32),
+                              traces.astype(np.int32))

@@ -1,0 +1,87 @@
+"""GPU parity of shared-prefix (cascade) decode attention against the oracle.  The oracle is
+given the same problem without sharing: one contiguous cache per sequence holding the prefix of
+its group followed by its suffix.  Tolerances as in test_gpu_parity.py."""
+import numpy as np
+import pytest
+
+from oracle import decode_attn
+from paper_2510_07356_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS, REL_L2, LSE_ABS = 1e-2, 5e-3, 4e-3
+
+
+@pytest.fixture(scope="module")
+def binding():
+    from paper_2510_07356_amd import binding as b
+    return b
+
+
+def check(sw, out, lse, tag):
+    c = sw.concatenated()
+    ref = decode_attn(c.q, c.k, c.v, c.kv_lens, c.scale)
+    got = out.double().cpu().numpy()
+    assert np.isfinite(got).all(), f"{tag}: non-finite"
+    err = got - ref.out
+    max_abs = np.abs(err).max()
+    rel = np.linalg.norm(err) / max(np.linalg.norm(ref.out), 1e-30)
+    worst = max([np.linalg.norm(err[b]) / np.linalg.norm(ref.out[b]) for b in range(c.batch) if c.kv_lens[b] > 0],
+                default=0.0)
+    print(f"{tag}: max_abs={max_abs:.3e} rel_l2={rel:.3e} worst_seq_rel_l2={worst:.3e}", flush=True)
+    assert max_abs <= MAX_ABS and rel <= REL_L2 and worst <= REL_L2, tag
+    gl = lse.double().cpu().numpy()
+    empty = c.kv_lens == 0
+    assert np.all(got[empty] == 0.0) and np.all(np.isneginf(gl[empty]))
+    assert np.abs(gl[~empty] - ref.lse[~empty]).max(initial=0.0) <= LSE_ABS, f"{tag}: lse"
+
+
+@pytest.mark.parametrize("paged", [False, True])
+@pytest.mark.parametrize("layout", ["head_major", "token_major"])
+def test_small_groups(binding, paged, layout):
+    """Group sizes 1..12 (1 to 4 MFMA column blocks with G = 5), empty prefixes, empty suffixes,
+    an entirely empty sequence, ragged tile tails."""
+    sizes = [1, 3, 4, 7, 12, 2]
+    prefixes = [100, 33, 0, 257, 64, 1]
+    rng = np.random.default_rng(3)
+    suffixes = rng.integers(0, 300, size=sum(sizes))
+    suffixes[0] = 0
+    suffixes[5] = 0          # group 2 has no prefix: this sequence is empty altogether
+    suffixes[9] = 1
+    sw = wl.make_shared_prefix("casc_small", 300, sizes, prefixes, suffixes, paged=paged, layout=layout)
+    for chunk in (0, 32, 256):
+        out, lse = binding.run_shared_prefix(sw, chunk_tokens=chunk)
+        check(sw, out, lse, f"casc_small/{layout}/paged{int(paged)}/c{chunk}")
+
+
+def test_group_of_four_heads_sixteen_samples(binding):
+    sw = wl.make_shared_prefix("casc_g4", 301, [16, 5], [700, 90], list(range(1, 22)), num_q_heads=32,
+                               num_kv_heads=8)
+    check(sw, *binding.run_shared_prefix(sw), "casc_g4")
+
+
+def test_single_group_equals_plain_attention_when_prefix_is_empty(binding):
+    """No prefix at all: the cascade entry point must reproduce the plain one."""
+    lens = [500, 31, 1200]
+    sw = wl.make_shared_prefix("casc_noprefix", 302, [3], [0], lens)
+    out, lse = binding.run_shared_prefix(sw)
+    check(sw, out, lse, "casc_noprefix")
+    plain, plain_lse = binding.run_workload(sw.base)
+    assert float((out - plain).abs().max()) <= 2e-3
+
+
+def test_too_large_group_is_rejected(binding):
+    sw = wl.make_shared_prefix("casc_big", 303, [13], [64], [10] * 13)       # 13 * 5 = 65 query rows > 64
+    with pytest.raises(binding.GqaError) as e:
+        binding.run_shared_prefix(sw)
+    assert e.value.status == binding.GQA_ERR_UNSUPPORTED
+
+
+def test_sampling_batch_full_size(binding):
+    """The benchmark workload: 12 prompts x 5 samples, every output element."""
+    sw = wl.make_sampling_batch()
+    out, lse = binding.run_shared_prefix(sw)
+    check(sw, out, lse, "sampling_12x5")
+    sw10 = wl.make_sampling_batch(seed=6, tasks=6, samples=10)
+    out, lse = binding.run_shared_prefix(sw10)
+    check(sw10, out, lse, "sampling_6x10")
