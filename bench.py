@@ -49,6 +49,63 @@ def measured_traffic(config_index: int):
     return int(v) if v is not None else None
 
 
+def bench_shared_prefix(args) -> int:
+    """Shared-prefix batch (12 prompts x 5 samples): the cascade entry point against the plain
+    entry point on the same problem with every sequence holding its own copy of the prefix."""
+    import torch
+    from paper_2510_07356_amd import binding, workloads
+    torch.cuda.set_device(0)
+    sw = workloads.make_sampling_batch(tasks=args.tasks, samples=args.samples)
+    w = sw.base
+    devs = [binding.shared_prefix_to_device(sw) for _ in range(2)]
+    d0 = devs[0]
+    cp = binding.make_cascade_params(d0["q"], d0["k"], d0["v"], d0["kp"], d0["vp"], w.max_kv_len,
+                                     int(sw.prefix_lens.max()), len(sw.prefix_lens), w.scale, 0, None, args.chunk)
+    ws = torch.empty(binding.gqa_cascade_workspace_bytes(cp), dtype=torch.uint8, device="cuda:0")
+    out = torch.empty((w.batch, w.num_q_heads, w.head_dim), dtype=torch.float32, device="cuda:0")
+    lse = torch.empty((w.batch, w.num_q_heads), dtype=torch.float32, device="cuda:0")
+    calls = [binding.CascadeCall(cp, d["q"], d["kp"], d["vp"], d["prefix_lens"], d["group_start"], sw.group_start,
+                                 d["k"], d["v"], d["kv_lens"], None, out, lse, ws) for d in devs]
+
+    def timed(fns):
+        for i in range(args.warmup):
+            fns[i % 2]()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            fns[i % 2]()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / args.steps
+
+    ms = timed(calls)
+    # the same problem without sharing
+    c = sw.concatenated()
+    cdevs = [binding.to_device(c) for _ in range(2)]
+    pp = binding.make_params(cdevs[0]["q"], cdevs[0]["k"], cdevs[0]["v"], c.max_kv_len, c.scale, 0, None, args.chunk, 0)
+    ws2 = torch.empty(binding.gqa_decode_workspace_bytes(pp), dtype=torch.uint8, device="cuda:0")
+    out2 = torch.empty_like(out)
+    plain = [binding.Call(pp, d["q"], d["k"], d["v"], d["kv_lens"], None, None, out2, None, ws2) for d in cdevs]
+    ms_plain = timed(plain)
+    calls[0](); plain[0]()
+    torch.cuda.synchronize()
+    result = {
+        "metric": "decode_attn_kv_read_throughput", "unit": "TB/s",
+        "value": round(sw.logical_kv_bytes / (ms * 1e-3) / 1e12, 4),
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{w.name}: {args.tasks} prompts x {args.samples} samples, shared prefix stored once, "
+                               f"Hq={w.num_q_heads} Hkv={w.num_kv_heads} D={w.head_dim}",
+                   "logical_kv_bytes": sw.logical_kv_bytes, "physical_kv_bytes": sw.physical_kv_bytes},
+        "physical_TBps": round(sw.physical_kv_bytes / (ms * 1e-3) / 1e12, 4),
+        "pct_of_hbm_peak_physical": round(100 * sw.physical_kv_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2),
+        "unshared_ms_per_step": round(ms_plain, 5),
+        "speedup_vs_unshared": round(ms_plain / ms, 4),
+        "max_abs_diff_vs_unshared": float((out - out2).abs().max()),
+    }
+    print(json.dumps(result), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -63,6 +120,10 @@ def main() -> int:
     ap.add_argument("--calibration-copy", type=int, default=0, metavar="MIB",
                     help="also run the plain copy kernel over this many MiB, three times (counter scaling in profiles)")
     ap.add_argument("--stream-read", action="store_true", help="also time the streaming-read probe over one cache copy")
+    ap.add_argument("--shared-prefix", action="store_true",
+                    help="benchmark the shared-prefix entry point on a tasks x samples batch instead")
+    ap.add_argument("--tasks", type=int, default=12)
+    ap.add_argument("--samples", type=int, default=5)
     ap.add_argument("--copies", type=int, default=0, help="cache copies to rotate over (0 = enough for 1 GiB)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -77,6 +138,8 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 3
+    if args.shared_prefix:
+        return bench_shared_prefix(args)
     torch.cuda.set_device(0)
     t_gen = time.time()
     w = workloads.make_config(args.config, layout=args.layout)

@@ -300,11 +300,16 @@ int make_cascade_plan(const gqa_cascade_params* cp, CascadePlan* plan) {
     int64_t shares = kMaxWorkers;
     const int fixed = p->chunk_tokens / gqa::kTileTokens;
     if (fixed > 0 && (max_tiles + fixed - 1) / fixed > shares) shares = (max_tiles + fixed - 1) / fixed;
-    plan->slots = shares + entries * p->num_kv_heads;
+    // rows: Hkv per suffix, Hkv * blocks per prefix; the blocks of all groups together are at most
+    // batch * group / 16 + num_groups
+    const int group = p->num_q_heads / p->num_kv_heads;
+    const int64_t rows = (int64_t)p->num_kv_heads *
+        ((int64_t)p->batch + ((int64_t)p->batch * group + 15) / 16 + cp->num_groups);
+    plan->slots = shares + rows;
     plan->header_bytes = 256;
-    plan->prefix_bytes = align_up(sizeof(int32_t) * ((size_t)entries + 1), 256);
-    plan->ml_bytes = align_up((size_t)plan->slots * gqa::kCascadeColumns * 2 * sizeof(float), 256);
-    plan->o_bytes = align_up((size_t)plan->slots * gqa::kCascadeColumns * gqa::kHeadDim * sizeof(float), 256);
+    plan->prefix_bytes = align_up(sizeof(int32_t) * 2 * ((size_t)entries + 1), 256);
+    plan->ml_bytes = align_up((size_t)plan->slots * 16 * 2 * sizeof(float), 256);
+    plan->o_bytes = align_up((size_t)plan->slots * 16 * gqa::kHeadDim * sizeof(float), 256);
     return GQA_OK;
 }
 

@@ -187,9 +187,10 @@ __device__ __forceinline__ StreamPos wave_stream_locate(const KernelArgs& a, int
 
 // Device-side view of one shared-prefix ("cascade") call: `base` describes the queries, the
 // per-sequence suffix caches (kv_lens = suffix lengths) and the outputs; the prefix of group j
-// lives at kp + j*kp_stride_g + g*kp_stride_h + t*kp_stride_t.  base.row_prefix holds one stream
-// position per entry (num_groups prefixes, then batch suffixes) plus the total.
-constexpr int kCascadeColumns = 64;      // query rows (samples x heads of a KV group) one prefix row can serve
+// lives at kp + j*kp_stride_g + g*kp_stride_h + t*kp_stride_t.  base.row_prefix holds two arrays
+// of entries + 1 ints (entries = num_groups prefixes, then batch suffixes): the stream position of
+// every entry, then the number of its first row.
+constexpr int kCascadeColumns = 64;      // query rows (samples x heads of a KV group) a group may have
 struct CascadeArgs {
     KernelArgs base;
     const uint16_t* kp;

@@ -97,6 +97,27 @@ __device__ __forceinline__ uint4 softmax_update(const f32x4 (&s)[2], SoftmaxStat
     return pb;
 }
 
+// V^T operands of the 8 M-tiles: 8x8 transpose of 16-bit elements in registers.  vt[2*x2] holds the
+// even column of each pair, vt[2*x2+1] the odd one (M-tile x <-> column d = 8c + x of piece c).
+__device__ __forceinline__ void transpose_values(const uint4 (&v)[8], uint4 (&vt)[8]) {
+    const uint32_t* v0 = reinterpret_cast<const uint32_t*>(&v[0]);
+    for (int x2 = 0; x2 < 4; ++x2) {
+        uint32_t* pe = reinterpret_cast<uint32_t*>(&vt[2 * x2]);
+        uint32_t* po = reinterpret_cast<uint32_t*>(&vt[2 * x2 + 1]);
+        for (int p2 = 0; p2 < 4; ++p2) {
+            const uint32_t lo = v0[(2 * p2) * 4 + x2];       // slot 2*p2, columns 2*x2, 2*x2+1
+            const uint32_t hi = v0[(2 * p2 + 1) * 4 + x2];   // slot 2*p2+1
+            pe[p2] = __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+            po[p2] = __builtin_amdgcn_perm(hi, lo, 0x07060302u);
+        }
+    }
+}
+
+// O^T += V^T P^T from already transposed operands: one MFMA per M-tile
+__device__ __forceinline__ void weighted_values_t(const uint4 (&vt)[8], const uint4& pb, SoftmaxState& st) {
+    for (int x = 0; x < 8; ++x) st.acc[x] = mfma16(vt[x], pb, st.acc[x]);
+}
+
 // O^T += V^T P^T: 8x8 transpose of 16-bit elements in registers, then one MFMA per M-tile
 __device__ __forceinline__ void weighted_values(const uint4 (&v)[8], const uint4& pb, SoftmaxState& st) {
     const uint32_t* v0 = reinterpret_cast<const uint32_t*>(&v[0]);

@@ -2,17 +2,20 @@
 //
 // The sequences of a batch come in groups -- the samples drawn for one prompt -- and all
 // sequences of a group share the prompt's keys and values, which are stored once.  Each sequence
-// attends over [shared prefix of its group ; its own suffix].  The prefix of a group is read ONCE
-// per KV head and serves all M * G query rows of the group (M samples, G query heads per KV
-// head): up to 64 rows = 4 MFMA column blocks per K/V tile, so this part is a real dense
-// contraction.  The suffixes are handled exactly as in gqa_partial_mfma.hip.
+// attends over [shared prefix of its group ; its own suffix].  One read of a prefix tile serves 16
+// query rows (one MFMA column block) taken from the M * G query rows of the group (M samples, G
+// query heads per KV head); a group with more than 16 such rows reads its prefix once per block of
+// 16, i.e. ceil(M * G / 16) times instead of M times.  Every tile of the stream, prefix or suffix,
+// then costs the same, which keeps the equal-share split balanced (a variant that served all 64
+// rows from one read made prefix tiles 4x as expensive and the kernel as slow as its slowest
+// wavefront).  The suffixes are handled exactly as in gqa_partial_mfma.hip.
 //
 // Stream split (see gqa_internal.h) over entries instead of sequences: entry e < num_groups is the
-// prefix of group e, entry num_groups + b the suffix of sequence b; every entry has Hkv rows, one
-// per KV head, of ceil(len / 32) tiles.  Row r = e * Hkv + g; a piece of share s writes its
-// partial results to slot s + r, 64 columns per slot (column f = m * G + head-in-group for a
-// prefix row, the head-in-group for a suffix row).  The combine kernel merges, for output row
-// (b, h), the pieces of the prefix row of b's group and of b's suffix row.
+// prefix of group e with Hkv * ceil(M*G/16) rows (row index = g * blocks + block), entry
+// num_groups + b the suffix of sequence b with Hkv rows; a row has ceil(len / 32) tiles.  Rows are
+// numbered in stream order; a piece of share s writes its partial results to slot s + row, 16
+// columns per slot.  The combine kernel merges, for output row (b, h), the pieces of the prefix
+// row that holds its column and of b's suffix row.
 #include "gqa_internal.h"
 #include "gqa_mfma_tile.h"
 
@@ -26,24 +29,36 @@ namespace {
 
 using namespace tile;
 
-constexpr int kMaxCb = kCascadeColumns / 16;      // MFMA column blocks a prefix row may need
+struct EntryShape { int len, rows; };    // tokens per row, rows of the entry
 
-__device__ __forceinline__ int entry_len_vec(const CascadeArgs& ca, int e) {      // per-lane loads
+__device__ __forceinline__ int blocks_of(int samples, int G) { return (min(samples * G, kCascadeColumns) + 15) >> 4; }
+
+__device__ __forceinline__ EntryShape entry_shape_vec(const CascadeArgs& ca, int e) {      // per-lane loads
     const KernelArgs& a = ca.base;
+    EntryShape s;
     if (e < ca.num_groups) {
-        const int m = ca.group_start[e + 1] - ca.group_start[e];
-        return m > 0 ? min(max(ca.prefix_lens[e], 0), ca.max_prefix_len) : 0;
+        const int m = max(ca.group_start[e + 1] - ca.group_start[e], 0);
+        s.rows = a.num_kv_heads * blocks_of(m, a.group);
+        s.len = m > 0 ? min(max(ca.prefix_lens[e], 0), ca.max_prefix_len) : 0;
+    } else {
+        s.rows = a.num_kv_heads;
+        s.len = clamped_len(a, e - ca.num_groups);
     }
-    return clamped_len(a, e - ca.num_groups);
+    return s;
 }
 
-__device__ __forceinline__ int entry_len_uniform(const CascadeArgs& ca, int e) {  // scalar-path loads
+__device__ __forceinline__ EntryShape entry_shape_uniform(const CascadeArgs& ca, int e) {  // scalar-path loads
     const KernelArgs& a = ca.base;
+    EntryShape s;
     if (e < ca.num_groups) {
-        const int m = uniform_i32(ca.group_start, e + 1) - uniform_i32(ca.group_start, e);
-        return m > 0 ? min(max(uniform_i32(ca.prefix_lens, e), 0), ca.max_prefix_len) : 0;
+        const int m = max(uniform_i32(ca.group_start, e + 1) - uniform_i32(ca.group_start, e), 0);
+        s.rows = a.num_kv_heads * blocks_of(m, a.group);
+        s.len = m > 0 ? min(max(uniform_i32(ca.prefix_lens, e), 0), ca.max_prefix_len) : 0;
+    } else {
+        s.rows = a.num_kv_heads;
+        s.len = uniform_len(a, e - ca.num_groups);
     }
-    return uniform_len(a, e - ca.num_groups);
+    return s;
 }
 
 __device__ __forceinline__ int cascade_total(const CascadeArgs& ca, int entries) {
@@ -51,65 +66,85 @@ __device__ __forceinline__ int cascade_total(const CascadeArgs& ca, int entries)
     int carry = 0;
     for (int base = 0; base < entries; base += 64) {
         const int e = base + lane;
-        const int n = (e < entries) ? ca.base.num_kv_heads * tiles_of(entry_len_vec(ca, e)) : 0;
+        int n = 0;
+        if (e < entries) {
+            const EntryShape s = entry_shape_vec(ca, e);
+            n = s.rows * tiles_of(s.len);
+        }
         carry += __shfl(wave_scan_incl(n), 63);
     }
     return carry;
 }
 
-// stream position -> (entry, kv head, tile, length); optionally writes every entry's position
-__device__ __forceinline__ StreamPos cascade_locate(const CascadeArgs& ca, int entries, int pos, int32_t* prefix_out) {
+struct CascadePos { int e, row_in_entry, tile, len, rows, first_row; };
+
+// stream position -> entry, row within it, tile, row length, rows of the entry, number of its first row;
+// optionally writes every entry's stream position and first row number
+__device__ __forceinline__ CascadePos cascade_locate(const CascadeArgs& ca, int entries, int pos,
+                                                     int32_t* tile_prefix_out, int32_t* row_prefix_out) {
     const int lane = threadIdx.x & 63;
-    int carry = 0;
-    StreamPos p;
-    p.b = 0; p.g = 0; p.tile = 0; p.len = 0;
+    int carry = 0, row_carry = 0;
+    CascadePos p;
+    p.e = 0; p.row_in_entry = 0; p.tile = 0; p.len = 0; p.rows = 1; p.first_row = 0;
     for (int base = 0; base < entries; base += 64) {
         const int e = base + lane;
-        const int len = (e < entries) ? entry_len_vec(ca, e) : 0;
-        const int tb = tiles_of(len);
-        const int n = ca.base.num_kv_heads * tb;
+        EntryShape s;
+        s.len = 0; s.rows = 0;
+        if (e < entries) s = entry_shape_vec(ca, e);
+        const int tb = tiles_of(s.len);
+        const int n = s.rows * tb;
         const int incl = wave_scan_incl(n);
         const int excl = carry + incl - n;
-        if (prefix_out != nullptr && e < entries) prefix_out[e] = excl;
+        const int rincl = wave_scan_incl(s.rows);
+        const int rexcl = row_carry + rincl - s.rows;
+        if (tile_prefix_out != nullptr && e < entries) { tile_prefix_out[e] = excl; row_prefix_out[e] = rexcl; }
         const bool hit = n > 0 && excl <= pos && pos < excl + n;
         const unsigned long long mask = __builtin_amdgcn_ballot_w64(hit);
         if (mask != 0) {
             const int src = __builtin_ctzll(mask);
             const int tbs = __shfl(tb, src), ex = __shfl(excl, src);
-            p.b = base + src;
-            p.g = (pos - ex) / tbs;
+            p.e = base + src;
+            p.row_in_entry = (pos - ex) / tbs;
             p.tile = (pos - ex) % tbs;
-            p.len = __shfl(len, src);
+            p.len = __shfl(s.len, src);
+            p.rows = __shfl(s.rows, src);
+            p.first_row = __shfl(rexcl, src);
         }
         carry += __shfl(incl, 63);
+        row_carry += __shfl(rincl, 63);
     }
-    if (prefix_out != nullptr && lane == 0) prefix_out[entries] = carry;
+    if (tile_prefix_out != nullptr && lane == 0) { tile_prefix_out[entries] = carry; row_prefix_out[entries] = row_carry; }
     return p;
 }
 
 struct CPiece {          // the part of a share inside one row; everything wave-uniform
-    int e, g, tile0, n, len;
+    int e, row_in_entry, rows, first_row;   // entry, row within it, rows of the entry, number of its first row
+    int tile0, n, len;
     bool prefix;         // row of a group's shared prefix
     int idx;             // group index (prefix) or sequence index (suffix)
+    int g;               // kv head
     int b0;              // first sequence whose queries this row serves
-    int ncols;           // query rows served: M * G (prefix) or G (suffix)
-    int ncb;             // MFMA column blocks: ceil(ncols / 16)
+    int col0, ncols;     // query rows served: flat columns [col0, col0 + ncols) of the group (sample * G + head)
 };
 
 __device__ __forceinline__ void describe(const CascadeArgs& ca, CPiece& p) {
     const int G = ca.base.group;
     p.prefix = p.e < ca.num_groups;
     if (p.prefix) {
+        const int blocks = p.rows / ca.base.num_kv_heads;
         p.idx = p.e;
+        p.g = p.row_in_entry / blocks;
         p.b0 = uniform_i32(ca.group_start, p.e);
         const int m = uniform_i32(ca.group_start, p.e + 1) - p.b0;
-        p.ncols = min(m * G, kCascadeColumns);
+        p.col0 = 16 * (p.row_in_entry - p.g * blocks);
+        p.ncols = min(min(m * G, kCascadeColumns) - p.col0, 16);
     } else {
         p.idx = p.e - ca.num_groups;
+        p.g = p.row_in_entry;
         p.b0 = p.idx;
+        p.col0 = 0;
         p.ncols = G;
     }
-    p.ncb = (p.ncols + 15) >> 4;
 }
 
 __device__ __forceinline__ void tile_blocks(const CascadeArgs& ca, const CPiece& p, int tile, bool idle, int (&blk)[2]) {
@@ -163,62 +198,58 @@ __device__ __forceinline__ void load_v(const CascadeArgs& ca, const CPiece& p, i
     }
 }
 
-// Q^T operands of all column blocks: column f = 16 cb + i serves sample f / G, head-in-group f % G
-__device__ __forceinline__ void load_q(const CascadeArgs& ca, const CPiece& p, int i, int kb, uint4 (&qf)[kMaxCb][4]) {
+// Q^T operand: MFMA column i serves flat column f = col0 + i of the row: sample f / G, head-in-group f % G
+__device__ __forceinline__ void load_q(const CascadeArgs& ca, const CPiece& p, int i, int kb, uint4 (&qf)[4]) {
     const KernelArgs& a = ca.base;
     const int G = a.group;
-#pragma unroll
-    for (int cb = 0; cb < kMaxCb; ++cb) {
-        for (int j = 0; j < 4; ++j) qf[cb][j] = make_uint4(0, 0, 0, 0);
-        const int f = 16 * cb + i;
-        if (f < p.ncols) {
-            const int m = f / G, hh = f - m * G;
-            const uint16_t* qrow = a.q + (int64_t)(p.b0 + m) * a.q_stride_b + (int64_t)(p.g * G + hh) * a.q_stride_h;
-            for (int j = 0; j < 4; ++j) qf[cb][j] = *reinterpret_cast<const uint4*>(qrow + 8 * (4 * j + kb));
-        }
+    for (int j = 0; j < 4; ++j) qf[j] = make_uint4(0, 0, 0, 0);
+    if (i < p.ncols) {
+        const int f = p.col0 + i;
+        const int m = f / G, hh = f - m * G;
+        const uint16_t* qrow = a.q + (int64_t)(p.b0 + m) * a.q_stride_b + (int64_t)(p.g * G + hh) * a.q_stride_h;
+        for (int j = 0; j < 4; ++j) qf[j] = *reinterpret_cast<const uint4*>(qrow + 8 * (4 * j + kb));
     }
 }
 
-__device__ __forceinline__ void settle_all_q(uint4 (&qf)[kMaxCb][4]) {
-#pragma unroll
-    for (int cb = 0; cb < kMaxCb; ++cb) settle_q(qf[cb]);
-}
-
-__device__ __forceinline__ void emit_piece(const CascadeArgs& ca, const CPiece& p, int share, SoftmaxState (&st)[kMaxCb],
+__device__ __forceinline__ void emit_piece(const CascadeArgs& ca, const CPiece& p, int share, SoftmaxState& st,
                                            int i, int kb) {
     const KernelArgs& a = ca.base;
-    const int64_t slot = (int64_t)share + (int64_t)p.e * a.num_kv_heads + p.g;
-#pragma unroll
-    for (int cb = 0; cb < kMaxCb; ++cb) {
-        if (cb >= p.ncb) continue;
-        float l = st[cb].l;
-        l += __shfl_xor(l, 16);
-        l += __shfl_xor(l, 32);
-        const int f = 16 * cb + i;
-        if (f < p.ncols) {
-            float* dst = a.part_o + (slot * kCascadeColumns + f) * kHeadDim + 32 * kb;
-            for (int r = 0; r < 4; ++r) {
-                float4 lo4, hi4;
-                lo4.x = st[cb].acc[0][r]; lo4.y = st[cb].acc[1][r]; lo4.z = st[cb].acc[2][r]; lo4.w = st[cb].acc[3][r];
-                hi4.x = st[cb].acc[4][r]; hi4.y = st[cb].acc[5][r]; hi4.z = st[cb].acc[6][r]; hi4.w = st[cb].acc[7][r];
-                *reinterpret_cast<float4*>(dst + 8 * r) = lo4;
-                *reinterpret_cast<float4*>(dst + 8 * r + 4) = hi4;
-            }
-            if (kb == 0)
-                *reinterpret_cast<float2*>(a.part_ml + (slot * kCascadeColumns + f) * 2) = make_float2(st[cb].m, l);
+    float l = st.l;
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+    if (i < p.ncols) {
+        const int64_t slot = (int64_t)share + p.first_row + p.row_in_entry;
+        float* dst = a.part_o + (slot * 16 + i) * kHeadDim + 32 * kb;
+        for (int r = 0; r < 4; ++r) {
+            float4 lo4, hi4;
+            lo4.x = st.acc[0][r]; lo4.y = st.acc[1][r]; lo4.z = st.acc[2][r]; lo4.w = st.acc[3][r];
+            hi4.x = st.acc[4][r]; hi4.y = st.acc[5][r]; hi4.z = st.acc[6][r]; hi4.w = st.acc[7][r];
+            *reinterpret_cast<float4*>(dst + 8 * r) = lo4;
+            *reinterpret_cast<float4*>(dst + 8 * r + 4) = hi4;
         }
+        if (kb == 0) *reinterpret_cast<float2*>(a.part_ml + (slot * 16 + i) * 2) = make_float2(st.m, l);
     }
 }
 
+// The piece that follows p inside a share that still has `left` tiles after p.
 __device__ __forceinline__ CPiece next_piece(const CascadeArgs& ca, const CPiece& p, int left, int entries) {
     CPiece q = p;
     q.tile0 = 0;
-    q.g = p.g + 1;
-    if (q.g == ca.base.num_kv_heads) {
-        q.g = 0;
-        do { ++q.e; q.len = entry_len_uniform(ca, q.e); } while (q.len == 0 && q.e + 1 < entries);
-        describe(ca, q);
+    q.row_in_entry = p.row_in_entry + 1;
+    if (q.row_in_entry == p.rows) {
+        q.row_in_entry = 0;
+        int first = p.first_row + p.rows;
+        EntryShape s;
+        do {
+            ++q.e;
+            s = entry_shape_uniform(ca, q.e);
+            if (s.len == 0) first += s.rows;          // rows of an empty entry still take numbers
+        } while (s.len == 0 && q.e + 1 < entries);
+        q.len = s.len;
+        q.rows = s.rows;
+        q.first_row = first;
     }
+    describe(ca, q);
     q.n = min(tiles_of(q.len), left);
     return q;
 }
@@ -232,42 +263,46 @@ __global__ __launch_bounds__(64 * GQA_MFMA_WAVES, 1) void partial_cascade_kernel
     const int entries = ca.num_groups + a.batch;
     const int worker = __builtin_amdgcn_readfirstlane(blockIdx.x * GQA_MFMA_WAVES + (threadIdx.x >> 6));
     const int workers = gridDim.x * GQA_MFMA_WAVES;
+    int32_t* const row_numbers = a.row_prefix + entries + 1;       // first row number of every entry
 
     const int total = __builtin_amdgcn_readfirstlane(cascade_total(ca, entries));
     const int share_tiles = share_tiles_for(total, a.fixed_share_tiles, workers);
     const int n_shares = (total + share_tiles - 1) / share_tiles;
     if (worker == 0) {
         if (lane == 0) { a.header[0] = total; a.header[1] = share_tiles; }
-        if (total == 0) (void)cascade_locate(ca, entries, 0, a.row_prefix);
+        if (total == 0) (void)cascade_locate(ca, entries, 0, a.row_prefix, row_numbers);
     }
 
     for (int share = worker; share < n_shares; share += workers) {
         int pos = share * share_tiles;
         const int end = min(pos + share_tiles, total);
-        const StreamPos sp = cascade_locate(ca, entries, pos, share == 0 ? a.row_prefix : nullptr);
+        const CascadePos sp = cascade_locate(ca, entries, pos, share == 0 ? a.row_prefix : nullptr, row_numbers);
         CPiece p;
-        p.e = __builtin_amdgcn_readfirstlane(sp.b);
-        p.g = __builtin_amdgcn_readfirstlane(sp.g);
+        p.e = __builtin_amdgcn_readfirstlane(sp.e);
+        p.row_in_entry = __builtin_amdgcn_readfirstlane(sp.row_in_entry);
+        p.rows = __builtin_amdgcn_readfirstlane(sp.rows);
+        p.first_row = __builtin_amdgcn_readfirstlane(sp.first_row);
         p.tile0 = __builtin_amdgcn_readfirstlane(sp.tile);
         p.len = __builtin_amdgcn_readfirstlane(sp.len);
         p.n = min(tiles_of(p.len) - p.tile0, end - pos);
         describe(ca, p);
 
-        uint4 kreg[2][4], vreg[8], qf[kMaxCb][4];
-        SoftmaxState st[kMaxCb];
+        uint4 kreg[2][4], vreg[8], qf[4];
+        SoftmaxState st;
         int blk[2] = {0, 0};
         if (PAGED && !p.prefix) tile_blocks(ca, p, 0, false, blk);
         load_k<PAGED>(ca, p, 0, false, blk, i, kb, kreg);
         load_v<PAGED>(ca, p, 0, false, blk, i, kb, vreg);
         load_q(ca, p, i, kb, qf);
-#pragma unroll
-        for (int cb = 0; cb < kMaxCb; ++cb) reset(st[cb]);
+        reset(st);
         bool has_next = pos + p.n < end;
         CPiece q = has_next ? next_piece(ca, p, end - pos - p.n, entries) : p;
         int t = 0;
-        settle_all_q(qf);
+        settle_q(qf);
 
         while (true) {
+            // as in gqa_partial_mfma.hip: the next tile is requested unconditionally (one cache line
+            // when nothing follows), V first (its registers are free after the transpose), K after the scores
             const bool last_of_piece = t + 1 == p.n;
             const bool cross = last_of_piece && has_next;
             const bool idle = last_of_piece && !has_next;
@@ -275,37 +310,14 @@ __global__ __launch_bounds__(64 * GQA_MFMA_WAVES, 1) void partial_cascade_kernel
             const int ldt = cross ? 0 : (last_of_piece ? t : t + 1);
             if (PAGED && !ld.prefix) tile_blocks(ca, ld, ldt, idle, blk);
 
-            f32x4 s[kMaxCb][2];
-#pragma unroll
-            for (int cb = 0; cb < kMaxCb; ++cb)
-                if (cb < p.ncb) scores(kreg, qf[cb], s[cb]);
-            load_k<PAGED>(ca, ld, ldt, idle, blk, i, kb, kreg);          // the K registers are free again
-            uint4 pb[kMaxCb];
-#pragma unroll
-            for (int cb = 0; cb < kMaxCb; ++cb)
-                if (cb < p.ncb) pb[cb] = softmax_update(s[cb], st[cb], kTileTokens * (p.tile0 + t), p.len, kb, c);
-            {   // O^T += V^T P^T for every column block: the transposed V operands are built once
-                const uint32_t* v0 = reinterpret_cast<const uint32_t*>(&vreg[0]);
-#pragma unroll
-                for (int x2 = 0; x2 < 4; ++x2) {
-                    uint4 even, odd;
-                    uint32_t* pe = reinterpret_cast<uint32_t*>(&even);
-                    uint32_t* po = reinterpret_cast<uint32_t*>(&odd);
-                    for (int p2 = 0; p2 < 4; ++p2) {
-                        const uint32_t lo = v0[(2 * p2) * 4 + x2];
-                        const uint32_t hi = v0[(2 * p2 + 1) * 4 + x2];
-                        pe[p2] = __builtin_amdgcn_perm(hi, lo, 0x05040100u);
-                        po[p2] = __builtin_amdgcn_perm(hi, lo, 0x07060302u);
-                    }
-#pragma unroll
-                    for (int cb = 0; cb < kMaxCb; ++cb)
-                        if (cb < p.ncb) {
-                            st[cb].acc[2 * x2] = mfma16(even, pb[cb], st[cb].acc[2 * x2]);
-                            st[cb].acc[2 * x2 + 1] = mfma16(odd, pb[cb], st[cb].acc[2 * x2 + 1]);
-                        }
-                }
-            }
+            uint4 vt[8];
+            transpose_values(vreg, vt);
             load_v<PAGED>(ca, ld, ldt, idle, blk, i, kb, vreg);
+            f32x4 s[2];
+            scores(kreg, qf, s);
+            load_k<PAGED>(ca, ld, ldt, idle, blk, i, kb, kreg);
+            const uint4 pb = softmax_update(s, st, kTileTokens * (p.tile0 + t), p.len, kb, c);
+            weighted_values_t(vt, pb, st);
 
             if (!last_of_piece) { ++t; continue; }
             emit_piece(ca, p, share, st, i, kb);
@@ -314,18 +326,18 @@ __global__ __launch_bounds__(64 * GQA_MFMA_WAVES, 1) void partial_cascade_kernel
             p = q;
             t = 0;
             load_q(ca, p, i, kb, qf);
-#pragma unroll
-            for (int cb = 0; cb < kMaxCb; ++cb) reset(st[cb]);
+            reset(st);
             has_next = pos + p.n < end;
             if (has_next) q = next_piece(ca, p, end - pos - p.n, entries);
-            settle_all_q(qf);
+            settle_q(qf);
         }
     }
 }
 
 // ---------------------------------------------------------------------------
-// Combine for the cascade: output row (b, h) merges column f = (b - b0) * G + hh of the pieces
-// of its group's prefix row and column hh of the pieces of its own suffix row.
+// Combine for the cascade: output row (b, h), flat column f = (b - b0) * G + hh of its group,
+// merges column f % 16 of the pieces of prefix row (g, f / 16) and column hh of the pieces of
+// b's suffix row g.
 // ---------------------------------------------------------------------------
 struct Merge { float M, den; float2 acc; };
 
@@ -342,7 +354,7 @@ __device__ __forceinline__ void merge_row(const KernelArgs& a, int start, int ti
 #pragma unroll
         for (int u = 0; u < kBatch; ++u) {
             const int cc = min(c0 + u, n - 1);
-            const int64_t w = ((int64_t)(s_first + cc) + r) * kCascadeColumns + col;
+            const int64_t w = ((int64_t)(s_first + cc) + r) * 16 + col;
             mlv[u] = ml[w];
             ov[u] = po[w * (kHeadDim / 2) + lane];
         }
@@ -373,8 +385,10 @@ __global__ __launch_bounds__(256) void combine_cascade_kernel(CascadeArgs ca) {
     if (row >= a.batch * a.num_q_heads) return;
     const int b = row / a.num_q_heads, h = row % a.num_q_heads;
     const int G = a.group, g = h / G, hh = h % G;
+    const int entries = ca.num_groups + a.batch;
     const int32_t* __restrict__ gs = ca.group_start;
-    const int32_t* __restrict__ pre = a.row_prefix;
+    const int32_t* __restrict__ pre = a.row_prefix;                 // stream position of every entry
+    const int32_t* __restrict__ num = a.row_prefix + entries + 1;   // first row number of every entry
     const int share_tiles = a.header[1];
     int lo = 0, hi = ca.num_groups;                 // group j with gs[j] <= b < gs[j + 1]
     while (hi - lo > 1) {
@@ -384,17 +398,20 @@ __global__ __launch_bounds__(256) void combine_cascade_kernel(CascadeArgs ca) {
     const int j = lo;
     Merge mg;
     mg.M = -INFINITY; mg.den = 0.f; mg.acc = make_float2(0.f, 0.f);
-    if (ca.num_groups > 0 && gs[j] <= b && b < gs[j + 1]) {
-        const int col = (b - gs[j]) * G + hh;
-        if (col < kCascadeColumns) {
-            const int tiles = (pre[j + 1] - pre[j]) / a.num_kv_heads;
-            merge_row(a, pre[j] + g * tiles, tiles, share_tiles, j * a.num_kv_heads + g, col, lane, mg);
+    if (gs[j] <= b && b < gs[j + 1]) {
+        const int f = (b - gs[j]) * G + hh;
+        const int rows = num[j + 1] - num[j];
+        const int blocks = rows / a.num_kv_heads;
+        if (f < kCascadeColumns && rows > 0) {
+            const int tiles = (pre[j + 1] - pre[j]) / rows;
+            const int idx = g * blocks + (f >> 4);
+            merge_row(a, pre[j] + idx * tiles, tiles, share_tiles, num[j] + idx, f & 15, lane, mg);
         }
     }
     {
         const int e = ca.num_groups + b;
         const int tiles = (pre[e + 1] - pre[e]) / a.num_kv_heads;
-        merge_row(a, pre[e] + g * tiles, tiles, share_tiles, e * a.num_kv_heads + g, hh, lane, mg);
+        merge_row(a, pre[e] + g * tiles, tiles, share_tiles, num[e] + g, hh, lane, mg);
     }
     const float inv = mg.den > 0.f ? 1.f / mg.den : 0.f;
     reinterpret_cast<float2*>(a.out)[(int64_t)row * (kHeadDim / 2) + lane] = make_float2(mg.acc.x * inv, mg.acc.y * inv);

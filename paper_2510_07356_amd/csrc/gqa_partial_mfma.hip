@@ -45,6 +45,9 @@
 #ifndef GQA_MFMA_EARLY_K             // 1: request the next K tile right after the scores, 0: after P.V
 #define GQA_MFMA_EARLY_K 1
 #endif
+#ifndef GQA_MFMA_EARLY_V             // 1: transpose V first and request the next V tile before the scores
+#define GQA_MFMA_EARLY_V 1
+#endif
 
 namespace gqa {
 
@@ -205,17 +208,28 @@ __global__ __launch_bounds__(64 * GQA_MFMA_WAVES, GQA_MFMA_WGS_PER_CU) void part
                 if (ahead_valid) tile_blocks(a, p, t + 2, false, blk_ahead);
             }
 
+#if GQA_MFMA_EARLY_V
+            uint4 vt[8];
+            transpose_values(vreg, vt);
+            load_v<PAGED>(a, ld, ldt, idle, blk, i, kb, vreg);    // the V registers are free again
+#endif
             f32x4 s[2];
             scores(kreg, qf, s);
 #if GQA_MFMA_EARLY_K
             load_k<PAGED>(a, ld, ldt, idle, blk, i, kb, kreg);    // the K registers are free again
 #endif
             const uint4 pb = softmax_update(s, st, kTileTokens * (p.tile0 + t), p.len, kb, c);
+#if GQA_MFMA_EARLY_V
+            weighted_values_t(vt, pb, st);
+#else
             weighted_values(vreg, pb, st);
+#endif
 #if !GQA_MFMA_EARLY_K
             load_k<PAGED>(a, ld, ldt, idle, blk, i, kb, kreg);
 #endif
+#if !GQA_MFMA_EARLY_V
             load_v<PAGED>(a, ld, ldt, idle, blk, i, kb, vreg);
+#endif
 
             if (!last_of_piece) { ++t; continue; }
             emit_piece(a, p, share, st, i, kb);
