@@ -219,6 +219,34 @@ int gqa_decode_attn_shared_prefix(const gqa_cascade_params* params,
                                   void* stream);
 
 /*
+ * Causal prefill attention (forward): the compute-bound companion of the decode
+ * path.  The prompt of every trace is prefilled once, and fine-tuning on the
+ * curated traces runs whole sequences of up to 32,768 tokens through the same
+ * attention (Section 4.1).  For every sequence b, token t and query head h
+ *     out[b, t, h, :] = attention of q[b, t, h, :] over keys/values 0 .. t of kv head h / group
+ * i.e. row t equals gqa_decode_attn of that query over the first t + 1 cached tokens.
+ *
+ *   q        [B, T, Hq, 128]  bf16, element strides q_stride_b / _t / _h
+ *   k, v     [B, T, Hkv, 128] bf16, strides likewise (16-byte aligned rows)
+ *   out      [B, T, Hq, 128]  fp32, strides o_stride_b / _t / _h (in floats, multiples of 4)
+ *   lse      [B, T, Hq] fp32 dense, may be NULL
+ * bf16 inputs, fp32 accumulation, probabilities rounded to bf16 for the second
+ * matrix product (as in the decode kernel).  No workspace.  Argument errors as
+ * in gqa_decode_attn; nothing is launched on error.
+ */
+typedef struct gqa_prefill_params {
+    int32_t batch, seq_len, num_q_heads, num_kv_heads, head_dim;   /* head_dim must be 128; group <= 16 */
+    float   scale;
+    int64_t q_stride_b, q_stride_t, q_stride_h;
+    int64_t k_stride_b, k_stride_t, k_stride_h;
+    int64_t v_stride_b, v_stride_t, v_stride_h;
+    int64_t o_stride_b, o_stride_t, o_stride_h;
+} gqa_prefill_params;
+
+int gqa_prefill_attn(const gqa_prefill_params* params, const void* q, const void* k, const void* v,
+                     float* out, float* lse, void* stream);
+
+/*
  * The step before attention in a decode layer: append the new token's key and
  * value rows to the cache and, optionally, apply the rotary position embedding
  * to the new key and to the query (the 32B model family whose traces the paper

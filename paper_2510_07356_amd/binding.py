@@ -25,7 +25,7 @@ GQA_ERR_LAUNCH = -4
 
 EXPORTS = ("gqa_decode_version", "gqa_decode_strerror", "gqa_decode_workspace_bytes",
            "gqa_decode_plan_info", "gqa_decode_attn", "gqa_decode_attn_timed",
-           "gqa_decode_kv_append", "gqa_cascade_workspace_bytes", "gqa_decode_attn_shared_prefix", "gqa_decode_stream_read", "gqa_decode_stream_copy", "gqa_timer_create", "gqa_timer_destroy", "gqa_timer_read")
+           "gqa_prefill_attn", "gqa_decode_kv_append", "gqa_cascade_workspace_bytes", "gqa_decode_attn_shared_prefix", "gqa_decode_stream_read", "gqa_decode_stream_copy", "gqa_timer_create", "gqa_timer_destroy", "gqa_timer_read")
 
 
 class gqa_decode_params(ctypes.Structure):
@@ -59,6 +59,17 @@ class gqa_cascade_params(ctypes.Structure):
         ("num_groups", ctypes.c_int32), ("max_prefix_len", ctypes.c_int32),
         ("kp_stride_g", ctypes.c_int64), ("kp_stride_h", ctypes.c_int64), ("kp_stride_t", ctypes.c_int64),
         ("vp_stride_g", ctypes.c_int64), ("vp_stride_h", ctypes.c_int64), ("vp_stride_t", ctypes.c_int64),
+    ]
+
+
+class gqa_prefill_params(ctypes.Structure):
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("seq_len", ctypes.c_int32), ("num_q_heads", ctypes.c_int32),
+        ("num_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("scale", ctypes.c_float),
+        ("q_stride_b", ctypes.c_int64), ("q_stride_t", ctypes.c_int64), ("q_stride_h", ctypes.c_int64),
+        ("k_stride_b", ctypes.c_int64), ("k_stride_t", ctypes.c_int64), ("k_stride_h", ctypes.c_int64),
+        ("v_stride_b", ctypes.c_int64), ("v_stride_t", ctypes.c_int64), ("v_stride_h", ctypes.c_int64),
+        ("o_stride_b", ctypes.c_int64), ("o_stride_t", ctypes.c_int64), ("o_stride_h", ctypes.c_int64),
     ]
 
 
@@ -99,6 +110,8 @@ def _load() -> ctypes.CDLL:
     lib.gqa_cascade_workspace_bytes.argtypes = [ctypes.POINTER(gqa_cascade_params)]
     lib.gqa_decode_attn_shared_prefix.restype = ctypes.c_int
     lib.gqa_decode_attn_shared_prefix.argtypes = [ctypes.POINTER(gqa_cascade_params)] + [vp] * 13 + [ctypes.c_size_t, vp]
+    lib.gqa_prefill_attn.restype = ctypes.c_int
+    lib.gqa_prefill_attn.argtypes = [ctypes.POINTER(gqa_prefill_params)] + [vp] * 6
     lib.gqa_decode_kv_append.restype = ctypes.c_int
     lib.gqa_decode_kv_append.argtypes = [ctypes.POINTER(gqa_append_params)] + [vp] * 10
     lib.gqa_decode_stream_read.restype = ctypes.c_int
@@ -329,6 +342,32 @@ def run_shared_prefix(sw, dev=None, chunk_tokens: int = 0, want_lse: bool = True
     CascadeCall(cp, dev["q"], dev["kp"], dev["vp"], dev["prefix_lens"], dev["group_start"], sw.group_start,
                 dev["k"], dev["v"], dev["kv_lens"], dev["block_table"], out, lse, ws)()
     return out, lse
+
+
+def gqa_prefill_attn(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, scale: float, out: torch.Tensor,
+                     lse: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None) -> None:
+    """q [B, T, Hq, D], k/v [B, T, Hkv, D] bf16 (any strides, dense last axis); out [B, T, Hq, D] fp32;
+    lse [B, T, Hq] fp32 dense or None."""
+    for t in (q, k, v):
+        if not t.is_cuda or t.dtype != torch.bfloat16 or t.stride(-1) != 1:
+            raise TypeError("bf16 device tensors with a dense last axis expected")
+    if not out.is_cuda or out.dtype != torch.float32 or out.stride(-1) != 1:
+        raise TypeError("out must be an fp32 device tensor with a dense last axis")
+    if lse is not None and (lse.dtype != torch.float32 or not lse.is_contiguous()):
+        raise TypeError("lse must be a dense fp32 tensor")
+    p = gqa_prefill_params()
+    p.batch, p.seq_len, p.num_q_heads, p.head_dim = q.shape
+    p.num_kv_heads = k.shape[2]
+    p.scale = float(scale)
+    p.q_stride_b, p.q_stride_t, p.q_stride_h = q.stride(0), q.stride(1), q.stride(2)
+    p.k_stride_b, p.k_stride_t, p.k_stride_h = k.stride(0), k.stride(1), k.stride(2)
+    p.v_stride_b, p.v_stride_t, p.v_stride_h = v.stride(0), v.stride(1), v.stride(2)
+    p.o_stride_b, p.o_stride_t, p.o_stride_h = out.stride(0), out.stride(1), out.stride(2)
+    s = stream if stream is not None else torch.cuda.current_stream(q.device)
+    rc = _lib.gqa_prefill_attn(ctypes.byref(p), q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(),
+                               lse.data_ptr() if lse is not None else None, s.cuda_stream)
+    if rc != GQA_OK:
+        raise GqaError(rc)
 
 
 def gqa_decode_kv_append(q_in: torch.Tensor, q_out: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor,

@@ -405,6 +405,38 @@ int gqa_decode_attn_shared_prefix(const gqa_cascade_params* cp, const void* q, c
     return GQA_OK;
 }
 
+int gqa_prefill_attn(const gqa_prefill_params* p, const void* q, const void* k, const void* v, float* out,
+                     float* lse, void* stream) {
+    if (p == nullptr) return GQA_ERR_INVALID_ARG;
+    if (p->batch < 1 || p->seq_len < 1 || p->num_q_heads < 1 || p->num_kv_heads < 1) return GQA_ERR_INVALID_ARG;
+    if (p->num_q_heads % p->num_kv_heads != 0 || !std::isfinite(p->scale)) return GQA_ERR_INVALID_ARG;
+    if (p->head_dim != gqa::kHeadDim) return GQA_ERR_UNSUPPORTED;
+    const int group = p->num_q_heads / p->num_kv_heads;
+    if (group > gqa::kMaxGroup) return GQA_ERR_UNSUPPORTED;
+    if (!q || !k || !v || !out) return GQA_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return GQA_ERR_INVALID_ARG;
+    if (!mult8(p->q_stride_b) || !mult8(p->q_stride_t) || !mult8(p->q_stride_h) || !mult8(p->k_stride_b) ||
+        !mult8(p->k_stride_t) || !mult8(p->k_stride_h) || !mult8(p->v_stride_b) || !mult8(p->v_stride_t) ||
+        !mult8(p->v_stride_h) || p->o_stride_b % 4 != 0 || p->o_stride_t % 4 != 0 || p->o_stride_h % 4 != 0)
+        return GQA_ERR_INVALID_ARG;
+    const int64_t blocks = ((int64_t)p->seq_len + 255) / 256;
+    if (8 * blocks * group * ((p->num_kv_heads + 7) / 8) * p->batch > 0x7fffffffLL) return GQA_ERR_UNSUPPORTED;
+    gqa::PrefillArgs a{};
+    a.q = static_cast<const uint16_t*>(q);
+    a.k = static_cast<const uint16_t*>(k);
+    a.v = static_cast<const uint16_t*>(v);
+    a.out = out;
+    a.lse = lse;
+    a.batch = p->batch; a.seq_len = p->seq_len;
+    a.num_q_heads = p->num_q_heads; a.num_kv_heads = p->num_kv_heads; a.group = group;
+    a.q_stride_b = p->q_stride_b; a.q_stride_t = p->q_stride_t; a.q_stride_h = p->q_stride_h;
+    a.k_stride_b = p->k_stride_b; a.k_stride_t = p->k_stride_t; a.k_stride_h = p->k_stride_h;
+    a.v_stride_b = p->v_stride_b; a.v_stride_t = p->v_stride_t; a.v_stride_h = p->v_stride_h;
+    a.o_stride_b = p->o_stride_b; a.o_stride_t = p->o_stride_t; a.o_stride_h = p->o_stride_h;
+    a.scale_log2e = p->scale * 1.4426950408889634f;
+    return gqa::launch_prefill(a, static_cast<hipStream_t>(stream)) == hipSuccess ? GQA_OK : GQA_ERR_LAUNCH;
+}
+
 int gqa_decode_kv_append(const gqa_append_params* p, const void* q_in, void* q_out, const void* k_new,
                          const void* v_new, void* k_cache, void* v_cache, const int32_t* kv_lens,
                          const int32_t* block_table, const float* cos_sin, void* stream) {

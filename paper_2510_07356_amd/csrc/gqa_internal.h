@@ -205,6 +205,22 @@ hipError_t launch_partial_cascade(const CascadeArgs& ca, int workgroups, hipStre
 hipError_t launch_combine_cascade(const CascadeArgs& ca, hipStream_t s);
 int partial_cascade_workers_per_group();
 
+// Device-side view of one causal prefill call.  Strides in elements (bf16 for q/k/v, fp32 for out).
+struct PrefillArgs {
+    const uint16_t* q;       // [batch, seq, Hq, D] via strides
+    const uint16_t* k;       // [batch, seq, Hkv, D]
+    const uint16_t* v;
+    float* out;              // [batch, seq, Hq, D] via strides
+    float* lse;              // [batch, seq, Hq] dense, may be null
+    int32_t batch, seq_len, num_q_heads, num_kv_heads, group;
+    int64_t q_stride_b, q_stride_t, q_stride_h;
+    int64_t k_stride_b, k_stride_t, k_stride_h;
+    int64_t v_stride_b, v_stride_t, v_stride_h;
+    int64_t o_stride_b, o_stride_t, o_stride_h;
+    float scale_log2e;
+};
+hipError_t launch_prefill(const PrefillArgs& a, hipStream_t s);
+
 // Device-side view of one append call.
 struct AppendArgs {
     const uint16_t* q_in;

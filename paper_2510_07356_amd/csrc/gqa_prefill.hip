@@ -1,0 +1,254 @@
+// Causal prefill attention (forward): every token t of a sequence attends over tokens 0..t.
+//
+// This is the compute-bound sibling of the decode kernels: the prompt is prefilled once before a
+// trace is generated, and fine-tuning on the traces runs full sequences of up to 32,768 tokens
+// through the same attention (Section 4.1 of the paper).  Row t of the result is by definition
+// the decode attention of query t over the first t + 1 keys.
+//
+// Decomposition.  One workgroup (4 wavefronts) owns 256 consecutive query rows of one query head,
+// 64 rows per wavefront, and walks the key/value tokens 0 .. (last row) in tiles of 64.  A K tile
+// is staged in LDS row-major, a V tile transposed ([column][token], transposed in registers with
+// v_perm_b32 on the way in), both double-buffered: the global loads of tile j+1 are issued before
+// the compute on tile j and written to the other buffer after it, one barrier per tile.
+//
+// Per wavefront and 32 tokens (v_mfma_f32_32x32x16_bf16; lane l: n = l % 32, kb = l / 32;
+// A[m][8kb+e], B[8kb+e][n], D[8(r/4) + 4kb + r%4][n] in register r):
+//   S^T[tok, q]  = K Q^T      A = K rows from LDS, B = Q^T kept in registers for the whole kernel
+//   online softmax per query row (= per lane column), base-2 exponentials, P rounded to bf16
+//   O^T[d, q]   += V^T P^T    A = V^T from LDS, B = P^T: with contraction slot (kb, e) of step s
+//                             standing for token 16s + 4kb + e (e < 4) or 16s + 8 + 4kb + e - 4,
+//                             the D registers 8s .. 8s+7 of S^T are exactly the B operand, so P
+//                             never moves between lanes.
+//
+// Scheduling across the chip: blockIdx % 8 is the XCD a workgroup lands on; KV head g is served
+// by XCD g % 8 only, so the five query heads of a KV group and all their row blocks share that
+// XCD's L2, and the row blocks are taken from the last (longest) to the first.
+#include "gqa_internal.h"
+#include "gqa_mfma_tile.h"
+
+namespace gqa {
+
+namespace {
+
+using namespace tile;
+
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+constexpr int kBM = 256;               // query rows per workgroup
+constexpr int kWaveRows = 64;          // query rows per wavefront (two MFMA column blocks)
+constexpr int kBN = 64;                // key tokens per LDS tile
+constexpr int kKStride = kHeadDim + 8; // bf16 elements per K row in LDS (272 B: conflict-free b128 reads)
+constexpr int kVStride = kBN + 4;      // bf16 elements per V^T row in LDS (136 B: conflict-free b64 reads)
+constexpr int kKTile = kBN * kKStride;         // elements
+constexpr int kVTile = kHeadDim * kVStride;    // elements
+
+__device__ __forceinline__ f32x16 mfma32(const uint4& a, const uint4& b, const f32x16& c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b),
+                                                   c, 0, 0, 0);
+}
+
+struct Staging {          // one K/V tile on its way from global memory to LDS (per thread)
+    uint4 k[4];           // token (tid / 16) + 16 i, 16-byte piece tid % 16
+    uint4 v[4];           // tokens 4 * (tid / 16) + i, 16-byte piece tid % 16
+};
+
+__device__ __forceinline__ void load_staging(const PrefillArgs& a, const uint16_t* kbase, const uint16_t* vbase,
+                                             int tok0, Staging& st) {
+    const int tid = threadIdx.x;
+    const int piece = tid & 15, grp = tid >> 4;
+    const int last = a.seq_len - 1;
+    for (int i = 0; i < 4; ++i) {
+        const int tk = min(tok0 + grp + 16 * i, last);                  // rows beyond the sequence re-read the last row
+        st.k[i] = *reinterpret_cast<const uint4*>(kbase + (int64_t)tk * a.k_stride_t + 8 * piece);
+        const int tv = min(tok0 + 4 * grp + i, last);
+        st.v[i] = *reinterpret_cast<const uint4*>(vbase + (int64_t)tv * a.v_stride_t + 8 * piece);
+    }
+}
+
+__device__ __forceinline__ void store_staging(const Staging& st, uint16_t* ks, uint16_t* vs) {
+    const int tid = threadIdx.x;
+    const int piece = tid & 15, grp = tid >> 4;
+    for (int i = 0; i < 4; ++i)
+        *reinterpret_cast<uint4*>(ks + (grp + 16 * i) * kKStride + 8 * piece) = st.k[i];
+    // 4 tokens x 8 columns -> 8 columns x 4 tokens, then one 8-byte store per column
+    const uint32_t* w = reinterpret_cast<const uint32_t*>(&st.v[0]);     // w[4 * token + pair]
+    for (int pr = 0; pr < 4; ++pr) {
+        const uint32_t t0 = w[0 + pr], t1 = w[4 + pr], t2 = w[8 + pr], t3 = w[12 + pr];
+        uint2 even, odd;                                                  // columns 2 pr and 2 pr + 1
+        even.x = __builtin_amdgcn_perm(t1, t0, 0x05040100u);
+        even.y = __builtin_amdgcn_perm(t3, t2, 0x05040100u);
+        odd.x = __builtin_amdgcn_perm(t1, t0, 0x07060302u);
+        odd.y = __builtin_amdgcn_perm(t3, t2, 0x07060302u);
+        *reinterpret_cast<uint2*>(vs + (8 * piece + 2 * pr) * kVStride + 4 * grp) = even;
+        *reinterpret_cast<uint2*>(vs + (8 * piece + 2 * pr + 1) * kVStride + 4 * grp) = odd;
+    }
+}
+
+__global__ __launch_bounds__(256, 1) void prefill_kernel(PrefillArgs a) {
+    extern __shared__ uint16_t lds[];           // [2][K tile] then [2][V^T tile]
+    uint16_t* const k_lds = lds;
+    uint16_t* const v_lds = lds + 2 * kKTile;
+
+    // task: XCD x serves KV heads x, x + 8, ...; row blocks from the last to the first
+    const int G = a.group;
+    const int n_qb = (a.seq_len + kBM - 1) / kBM;
+    const int xcd = blockIdx.x & 7;
+    int s = blockIdx.x >> 3;
+    const int hh = s % G; s /= G;
+    const int qb = n_qb - 1 - (s % n_qb); s /= n_qb;
+    const int heads_per_xcd = (a.num_kv_heads + 7) >> 3;
+    const int g = xcd + 8 * (s % heads_per_xcd); s /= heads_per_xcd;
+    const int b = s;
+    if (g >= a.num_kv_heads) return;
+    const int h = g * G + hh;
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = lane & 31, kb = lane >> 5;
+    const int q0 = qb * kBM + wave * kWaveRows;              // first query row of this wavefront
+    const int q_last = min(q0 + kWaveRows, a.seq_len) - 1;   // may be < q0: wavefront without rows
+    const float c = a.scale_log2e;
+
+    const uint16_t* qbase = a.q + (int64_t)b * a.q_stride_b + (int64_t)h * a.q_stride_h;
+    const uint16_t* kbase = a.k + (int64_t)b * a.k_stride_b + (int64_t)g * a.k_stride_h;
+    const uint16_t* vbase = a.v + (int64_t)b * a.v_stride_b + (int64_t)g * a.v_stride_h;
+
+    // Q^T as B operands: column n of block nt is query row q0 + 32 nt + n, step st covers columns 16 st + 8 kb + e
+    uint4 qf[2][8];
+    for (int nt = 0; nt < 2; ++nt) {
+        const int qr = min(q0 + 32 * nt + n, a.seq_len - 1);
+        const uint16_t* qrow = qbase + (int64_t)qr * a.q_stride_t;
+        for (int st = 0; st < 8; ++st) qf[nt][st] = *reinterpret_cast<const uint4*>(qrow + 16 * st + 8 * kb);
+    }
+
+    f32x16 acc[2][4];
+    for (int nt = 0; nt < 2; ++nt)
+        for (int dt = 0; dt < 4; ++dt)
+            for (int r = 0; r < 16; ++r) acc[nt][dt][r] = 0.f;
+    float m[2] = {-INFINITY, -INFINITY}, l[2] = {0.f, 0.f};
+
+    const int kv_end = min(qb * kBM + kBM, a.seq_len);        // keys this workgroup needs: [0, kv_end)
+    const int n_tiles = (kv_end + kBN - 1) / kBN;
+
+    Staging stg;
+    load_staging(a, kbase, vbase, 0, stg);
+    store_staging(stg, k_lds, v_lds);
+    __syncthreads();
+
+    for (int tile = 0; tile < n_tiles; ++tile) {
+        const int buf = tile & 1;
+        const bool more = tile + 1 < n_tiles;
+        if (more) load_staging(a, kbase, vbase, (tile + 1) * kBN, stg);
+
+        const uint16_t* ks = k_lds + buf * kKTile;
+        const uint16_t* vs = v_lds + buf * kVTile;
+        for (int tt = 0; tt < 2; ++tt) {                      // two 32-token MFMA tiles per LDS tile
+            const int tok0 = tile * kBN + 32 * tt;
+            if (tok0 > q_last) break;                         // entirely above the diagonal for this wavefront
+            // scores S^T[tok, q] for both column blocks; the K operand is read once per step
+            f32x16 sc[2];
+            for (int nt = 0; nt < 2; ++nt)
+                for (int r = 0; r < 16; ++r) sc[nt][r] = 0.f;
+#pragma unroll
+            for (int st = 0; st < 8; ++st) {
+                const uint4 ka = *reinterpret_cast<const uint4*>(ks + (32 * tt + n) * kKStride + 16 * st + 8 * kb);
+                sc[0] = mfma32(ka, qf[0][st], sc[0]);
+                sc[1] = mfma32(ka, qf[1][st], sc[1]);
+            }
+            uint4 pb[2][2];                                   // P^T operands [column block][k-step]
+            const bool diagonal = tok0 + 31 > q0;             // some (token, row) pair of this tile is masked
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt) {
+                const int qrow = q0 + 32 * nt + n;
+                float tmax = -INFINITY;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    float x = sc[nt][r] * c;
+                    if (diagonal) {
+                        const int tok = tok0 + 8 * (r >> 2) + 4 * kb + (r & 3);
+                        x = (tok <= qrow) ? x : -INFINITY;
+                    }
+                    sc[nt][r] = x;
+                    tmax = fmaxf(tmax, x);
+                }
+                tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+                const float mn = fmaxf(m[nt], tmax);
+                const float ms = (mn == -INFINITY) ? 0.f : mn;       // a row with nothing visible yet
+                if (__builtin_amdgcn_ballot_w64(mn > m[nt]) != 0) {
+                    const float alpha = exp2f(m[nt] - ms);
+                    l[nt] *= alpha;
+                    for (int dt = 0; dt < 4; ++dt) acc[nt][dt] *= alpha;
+                    m[nt] = mn;
+                }
+                float p[16];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) p[r] = exp2f(sc[nt][r] - ms);
+#pragma unroll
+                for (int ks2 = 0; ks2 < 2; ++ks2) {
+                    uint4 w;
+                    w.x = pack_bf16(p[8 * ks2 + 0], p[8 * ks2 + 1]);
+                    w.y = pack_bf16(p[8 * ks2 + 2], p[8 * ks2 + 3]);
+                    w.z = pack_bf16(p[8 * ks2 + 4], p[8 * ks2 + 5]);
+                    w.w = pack_bf16(p[8 * ks2 + 6], p[8 * ks2 + 7]);
+                    pb[nt][ks2] = w;
+                    l[nt] += (bf16_lo(w.x) + bf16_hi(w.x)) + (bf16_lo(w.y) + bf16_hi(w.y)) +
+                             (bf16_lo(w.z) + bf16_hi(w.z)) + (bf16_lo(w.w) + bf16_hi(w.w));
+                }
+            }
+            // O^T += V^T P^T; the V^T operand is read once per (column tile, step) and serves both blocks
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                for (int ks2 = 0; ks2 < 2; ++ks2) {
+                    const uint16_t* vp = vs + (32 * dt + n) * kVStride + 32 * tt + 16 * ks2 + 4 * kb;
+                    const uint2 lo = *reinterpret_cast<const uint2*>(vp);
+                    const uint2 hi = *reinterpret_cast<const uint2*>(vp + 8);
+                    const uint4 va = make_uint4(lo.x, lo.y, hi.x, hi.y);
+                    acc[0][dt] = mfma32(va, pb[0][ks2], acc[0][dt]);
+                    acc[1][dt] = mfma32(va, pb[1][ks2], acc[1][dt]);
+                }
+        }
+        if (more) store_staging(stg, k_lds + (buf ^ 1) * kKTile, v_lds + (buf ^ 1) * kVTile);
+        __syncthreads();
+    }
+
+    // epilogue: normalise and store; lane holds query row q0 + 32 nt + n, columns 32 dt + 8 (r/4) + 4 kb + r%4
+    for (int nt = 0; nt < 2; ++nt) {
+        float lt = l[nt];
+        lt += __shfl_xor(lt, 32);
+        const int qrow = q0 + 32 * nt + n;
+        if (qrow < a.seq_len) {
+            const float inv = lt > 0.f ? 1.f / lt : 0.f;
+            float* orow = a.out + (int64_t)b * a.o_stride_b + (int64_t)qrow * a.o_stride_t + (int64_t)h * a.o_stride_h;
+            for (int dt = 0; dt < 4; ++dt)
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    float4 o;
+                    o.x = acc[nt][dt][4 * r4 + 0] * inv; o.y = acc[nt][dt][4 * r4 + 1] * inv;
+                    o.z = acc[nt][dt][4 * r4 + 2] * inv; o.w = acc[nt][dt][4 * r4 + 3] * inv;
+                    *reinterpret_cast<float4*>(orow + 32 * dt + 8 * r4 + 4 * kb) = o;
+                }
+            if (a.lse != nullptr && kb == 0)
+                a.lse[((int64_t)b * a.seq_len + qrow) * a.num_q_heads + h] =
+                    lt > 0.f ? 0.6931471805599453f * (m[nt] + log2f(lt)) : -INFINITY;
+        }
+    }
+}
+
+constexpr size_t kPrefillLds = (size_t)(2 * kKTile + 2 * kVTile) * sizeof(uint16_t);
+
+}  // namespace
+
+hipError_t launch_prefill(const PrefillArgs& a, hipStream_t s) {
+    static bool configured = false;
+    if (!configured) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_kernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPrefillLds);
+        configured = true;
+    }
+    const int n_qb = (a.seq_len + kBM - 1) / kBM;
+    const int heads_per_xcd = (a.num_kv_heads + 7) / 8;
+    const int64_t grid = 8LL * a.group * n_qb * heads_per_xcd * a.batch;
+    hipLaunchKernelGGL(prefill_kernel, dim3((unsigned)grid), dim3(256), kPrefillLds, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace gqa

@@ -23,7 +23,7 @@ def lib():
 def declared_functions():
     text = open(HEADER).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(gqa_(?:decode|timer|cascade)_\w+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(gqa_(?:decode|timer|cascade|prefill)_\w+)\s*\(", text)))
 
 
 def test_header_and_library_agree(lib):

@@ -1,0 +1,108 @@
+"""GPU parity of causal prefill attention.  Row t of causal attention is, by definition, the decode
+attention of query t over the first t + 1 keys, so the (pinned) decode oracle serves: it is called
+with one "sequence" per checked row, all sharing the same K/V cache (batch stride 0) with
+kv_len = t + 1.  Small cases check every row; the 32,768-token case checks sampled rows."""
+import numpy as np
+import pytest
+
+from oracle import decode_attn
+from paper_2510_07356_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS, REL_L2, LSE_ABS = 1e-2, 5e-3, 4e-3
+
+
+@pytest.fixture(scope="module")
+def binding():
+    from paper_2510_07356_amd import binding as b
+    return b
+
+
+def make_inputs(seed, B, T, Hq, Hkv, D=128):
+    rng = np.random.default_rng(seed)
+    q = wl.f32_to_bf16_bits(rng.standard_normal((B, T, Hq, D), dtype=np.float32))
+    k = wl.f32_to_bf16_bits(rng.standard_normal((B, T, Hkv, D), dtype=np.float32))
+    v = wl.f32_to_bf16_bits(rng.standard_normal((B, T, Hkv, D), dtype=np.float32))
+    return q, k, v
+
+
+def oracle_rows(q, k, v, b, rows, scale):
+    """Causal attention rows `rows` of sequence b via the decode oracle."""
+    rows = np.asarray(rows)
+    qq = np.ascontiguousarray(q[b, rows])                                  # [R, Hq, D]
+    kk = np.broadcast_to(k[b].transpose(1, 0, 2)[None], (len(rows),) + k[b].transpose(1, 0, 2).shape)
+    vv = np.broadcast_to(v[b].transpose(1, 0, 2)[None], kk.shape)          # [R, Hkv, T, D], batch stride 0
+    return decode_attn(qq, kk, vv, rows + 1, scale)
+
+
+def run(binding, q, k, v, scale):
+    import torch
+    dq, dk, dv = (binding._bf16_view(x).to("cuda:0") for x in (q, k, v))
+    B, T, Hq, D = q.shape
+    out = torch.full((B, T, Hq, D), float("nan"), dtype=torch.float32, device="cuda:0")
+    lse = torch.full((B, T, Hq), float("nan"), dtype=torch.float32, device="cuda:0")
+    binding.gqa_prefill_attn(dq, dk, dv, scale, out, lse)
+    torch.cuda.synchronize()
+    return out, lse
+
+
+def check_rows(out, lse, ref, b, rows, tag):
+    got = out[b].double().cpu().numpy()[rows]
+    assert np.isfinite(got).all(), f"{tag}: non-finite"
+    err = got - ref.out
+    max_abs = np.abs(err).max()
+    rel = np.linalg.norm(err) / np.linalg.norm(ref.out)
+    worst = max(np.linalg.norm(err[i]) / np.linalg.norm(ref.out[i]) for i in range(len(rows)))
+    print(f"{tag}: rows={len(rows)} max_abs={max_abs:.3e} rel_l2={rel:.3e} worst_row_rel_l2={worst:.3e}", flush=True)
+    assert max_abs <= MAX_ABS and rel <= REL_L2 and worst <= REL_L2, tag
+    gl = lse[b].double().cpu().numpy()[rows]
+    assert np.abs(gl - ref.lse).max() <= LSE_ABS, f"{tag}: lse"
+
+
+@pytest.mark.parametrize("T", [1, 31, 64, 257, 700])
+def test_every_row_small(binding, T):
+    scale = float(np.float32(1.0 / np.sqrt(128)))
+    q, k, v = make_inputs(400 + T, 2, T, 10, 2)
+    out, lse = run(binding, q, k, v, scale)
+    for b in range(2):
+        rows = np.arange(T)
+        check_rows(out, lse, oracle_rows(q, k, v, b, rows, scale), b, rows, f"prefill_T{T}_b{b}")
+
+
+def test_first_row_is_the_first_value_row(binding):
+    scale = 0.25
+    q, k, v = make_inputs(450, 1, 300, 8, 8)
+    out, _ = run(binding, q, k, v, scale)
+    np.testing.assert_array_equal(out[0, 0].cpu().numpy(), wl.bf16_bits_to_f32(v[0, 0]))
+
+
+def test_strided_inputs_and_group_sizes(binding):
+    """Token-major projections sliced out of a fused QKV buffer, group sizes 1, 4 and 16."""
+    import torch
+    scale = float(np.float32(1.0 / np.sqrt(128)))
+    for Hq, Hkv in ((4, 4), (16, 4), (16, 1)):
+        T = 200
+        q, k, v = make_inputs(460 + Hq + Hkv, 1, T, Hq, Hkv)
+        fused = torch.zeros((1, T, Hq + 2 * Hkv, 128), dtype=torch.bfloat16, device="cuda:0")
+        fused[:, :, :Hq] = binding._bf16_view(q).to("cuda:0")
+        fused[:, :, Hq:Hq + Hkv] = binding._bf16_view(k).to("cuda:0")
+        fused[:, :, Hq + Hkv:] = binding._bf16_view(v).to("cuda:0")
+        out = torch.empty((1, T, Hq, 128), dtype=torch.float32, device="cuda:0")
+        lse = torch.empty((1, T, Hq), dtype=torch.float32, device="cuda:0")
+        binding.gqa_prefill_attn(fused[:, :, :Hq], fused[:, :, Hq:Hq + Hkv], fused[:, :, Hq + Hkv:], scale, out, lse)
+        rows = np.arange(T)
+        check_rows(out, lse, oracle_rows(q, k, v, 0, rows, scale), 0, rows, f"prefill_fused_{Hq}_{Hkv}")
+
+
+def test_long_sequence_sampled_rows(binding):
+    """32,768 tokens, the 32B head shape: sampled rows (block edges, the diagonal of every kind of
+    tile, the last rows) against the oracle."""
+    scale = float(np.float32(1.0 / np.sqrt(128)))
+    T = 32768
+    q, k, v = make_inputs(470, 1, T, 40, 8)
+    out, lse = run(binding, q, k, v, scale)
+    rng = np.random.default_rng(1)
+    rows = np.unique(np.concatenate([[0, 1, 31, 32, 63, 64, 255, 256, 257, 16383, 16384, T - 257, T - 256, T - 1],
+                                     rng.integers(0, T, size=50)]))
+    check_rows(out, lse, oracle_rows(q, k, v, 0, rows, scale), 0, rows, "prefill_32k")
