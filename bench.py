@@ -106,6 +106,41 @@ def bench_shared_prefix(args) -> int:
     return 0
 
 
+def bench_prefill(args) -> int:
+    """Causal prefill attention over one sequence of --seq-len tokens with the 32B head shape."""
+    import numpy as np
+    import torch
+    from paper_2510_07356_amd import binding
+    torch.cuda.set_device(0)
+    T, Hq, Hkv, D = args.seq_len, 40, 8, 128
+    g = torch.Generator(device="cuda:0").manual_seed(11)
+    q = torch.randn((1, T, Hq, D), generator=g, device="cuda:0", dtype=torch.float32).to(torch.bfloat16)
+    k = torch.randn((1, T, Hkv, D), generator=g, device="cuda:0", dtype=torch.float32).to(torch.bfloat16)
+    v = torch.randn((1, T, Hkv, D), generator=g, device="cuda:0", dtype=torch.float32).to(torch.bfloat16)
+    out = torch.empty((1, T, Hq, D), dtype=torch.float32, device="cuda:0")
+    scale = float(np.float32(1.0 / np.sqrt(D)))
+    for _ in range(args.warmup):
+        binding.gqa_prefill_attn(q, k, v, scale, out)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        binding.gqa_prefill_attn(q, k, v, scale, out)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    flops = 4.0 * D * Hq * T * (T + 1) / 2.0            # two matrix products over the causal half
+    tflops = flops / (ms * 1e-3) / 1e12
+    print(json.dumps({
+        "metric": "causal_prefill_attention_throughput", "value": round(tflops, 2), "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"causal prefill, one sequence of {T} tokens, Hq={Hq} Hkv={Hkv} D={D}", "flops": flops},
+        "tokens_per_s": round(T / (ms * 1e-3), 1),
+        "roofline": {"kernel": "prefill_kernel", "bound": "mfma", "achieved": round(tflops, 2), "peak": 2500.0,
+                     "unit": "TFLOP/s", "frac": round(tflops / 2500.0, 4), "traffic": None},
+    }), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -122,6 +157,8 @@ def main() -> int:
     ap.add_argument("--stream-read", action="store_true", help="also time the streaming-read probe over one cache copy")
     ap.add_argument("--shared-prefix", action="store_true",
                     help="benchmark the shared-prefix entry point on a tasks x samples batch instead")
+    ap.add_argument("--prefill", action="store_true", help="benchmark causal prefill attention instead")
+    ap.add_argument("--seq-len", type=int, default=32768)
     ap.add_argument("--tasks", type=int, default=12)
     ap.add_argument("--samples", type=int, default=5)
     ap.add_argument("--copies", type=int, default=0, help="cache copies to rotate over (0 = enough for 1 GiB)")
@@ -140,6 +177,8 @@ def main() -> int:
         return 3
     if args.shared_prefix:
         return bench_shared_prefix(args)
+    if args.prefill:
+        return bench_prefill(args)
     torch.cuda.set_device(0)
     t_gen = time.time()
     w = workloads.make_config(args.config, layout=args.layout)

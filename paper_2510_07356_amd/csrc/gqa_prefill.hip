@@ -5,11 +5,12 @@
 // through the same attention (Section 4.1 of the paper).  Row t of the result is by definition
 // the decode attention of query t over the first t + 1 keys.
 //
-// Decomposition.  One workgroup (4 wavefronts) owns 256 consecutive query rows of one query head,
-// 64 rows per wavefront, and walks the key/value tokens 0 .. (last row) in tiles of 64.  A K tile
-// is staged in LDS row-major, a V tile transposed ([column][token], transposed in registers with
-// v_perm_b32 on the way in), both double-buffered: the global loads of tile j+1 are issued before
-// the compute on tile j and written to the other buffer after it, one barrier per tile.
+// Decomposition.  One workgroup (8 wavefronts, two per SIMD so that one wavefront's exponentials
+// overlap the other's matrix products) owns 256 consecutive query rows of one query head, 32 rows
+// per wavefront, and walks the key/value tokens 0 .. (last row) in tiles of 128.  A K tile is staged
+// in LDS row-major, a V tile transposed ([column][token], transposed in registers with v_perm_b32
+// on the way in), both double-buffered: the global loads of tile j+1 are issued before the compute
+// on tile j and written to the other buffer after it, one barrier per tile.
 //
 // Per wavefront and 32 tokens (v_mfma_f32_32x32x16_bf16; lane l: n = l % 32, kb = l / 32;
 // A[m][8kb+e], B[8kb+e][n], D[8(r/4) + 4kb + r%4][n] in register r):
@@ -35,8 +36,9 @@ using namespace tile;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 constexpr int kBM = 256;               // query rows per workgroup
-constexpr int kWaveRows = 64;          // query rows per wavefront (two MFMA column blocks)
-constexpr int kBN = 64;                // key tokens per LDS tile
+constexpr int kWaveRows = 32;          // query rows per wavefront (one MFMA column block)
+constexpr int kPrefillThreads = 64 * (kBM / kWaveRows);
+constexpr int kBN = 128;               // key tokens per LDS tile
 constexpr int kKStride = kHeadDim + 8; // bf16 elements per K row in LDS (272 B: conflict-free b128 reads)
 constexpr int kVStride = kBN + 4;      // bf16 elements per V^T row in LDS (136 B: conflict-free b64 reads)
 constexpr int kKTile = kBN * kKStride;         // elements
@@ -47,8 +49,14 @@ __device__ __forceinline__ f32x16 mfma32(const uint4& a, const uint4& b, const f
                                                    c, 0, 0, 0);
 }
 
+// acc + lo + hi of a packed bf16 pair, exact products with 1.0, fp32 accumulation
+__device__ __forceinline__ float pair_sum(uint32_t pair, float acc) {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pair), __builtin_bit_cast(bf16x2, 0x3F803F80u),
+                                           acc, false);
+}
+
 struct Staging {          // one K/V tile on its way from global memory to LDS (per thread)
-    uint4 k[4];           // token (tid / 16) + 16 i, 16-byte piece tid % 16
+    uint4 k[4];           // token (tid / 16) + 32 i, 16-byte piece tid % 16
     uint4 v[4];           // tokens 4 * (tid / 16) + i, 16-byte piece tid % 16
 };
 
@@ -58,7 +66,7 @@ __device__ __forceinline__ void load_staging(const PrefillArgs& a, const uint16_
     const int piece = tid & 15, grp = tid >> 4;
     const int last = a.seq_len - 1;
     for (int i = 0; i < 4; ++i) {
-        const int tk = min(tok0 + grp + 16 * i, last);                  // rows beyond the sequence re-read the last row
+        const int tk = min(tok0 + grp + 32 * i, last);                  // rows beyond the sequence re-read the last row
         st.k[i] = *reinterpret_cast<const uint4*>(kbase + (int64_t)tk * a.k_stride_t + 8 * piece);
         const int tv = min(tok0 + 4 * grp + i, last);
         st.v[i] = *reinterpret_cast<const uint4*>(vbase + (int64_t)tv * a.v_stride_t + 8 * piece);
@@ -69,22 +77,24 @@ __device__ __forceinline__ void store_staging(const Staging& st, uint16_t* ks, u
     const int tid = threadIdx.x;
     const int piece = tid & 15, grp = tid >> 4;
     for (int i = 0; i < 4; ++i)
-        *reinterpret_cast<uint4*>(ks + (grp + 16 * i) * kKStride + 8 * piece) = st.k[i];
+        *reinterpret_cast<uint4*>(ks + (grp + 32 * i) * kKStride + 8 * piece) = st.k[i];
     // 4 tokens x 8 columns -> 8 columns x 4 tokens, then one 8-byte store per column
-    const uint32_t* w = reinterpret_cast<const uint32_t*>(&st.v[0]);     // w[4 * token + pair]
-    for (int pr = 0; pr < 4; ++pr) {
-        const uint32_t t0 = w[0 + pr], t1 = w[4 + pr], t2 = w[8 + pr], t3 = w[12 + pr];
-        uint2 even, odd;                                                  // columns 2 pr and 2 pr + 1
+    auto column_pair = [&](uint32_t t0, uint32_t t1, uint32_t t2, uint32_t t3, int pr) {
+        uint2 even, odd;                                                  // columns 2 pr and 2 pr + 1, tokens 0..3
         even.x = __builtin_amdgcn_perm(t1, t0, 0x05040100u);
         even.y = __builtin_amdgcn_perm(t3, t2, 0x05040100u);
         odd.x = __builtin_amdgcn_perm(t1, t0, 0x07060302u);
         odd.y = __builtin_amdgcn_perm(t3, t2, 0x07060302u);
         *reinterpret_cast<uint2*>(vs + (8 * piece + 2 * pr) * kVStride + 4 * grp) = even;
         *reinterpret_cast<uint2*>(vs + (8 * piece + 2 * pr + 1) * kVStride + 4 * grp) = odd;
-    }
+    };
+    column_pair(st.v[0].x, st.v[1].x, st.v[2].x, st.v[3].x, 0);
+    column_pair(st.v[0].y, st.v[1].y, st.v[2].y, st.v[3].y, 1);
+    column_pair(st.v[0].z, st.v[1].z, st.v[2].z, st.v[3].z, 2);
+    column_pair(st.v[0].w, st.v[1].w, st.v[2].w, st.v[3].w, 3);
 }
 
-__global__ __launch_bounds__(256, 1) void prefill_kernel(PrefillArgs a) {
+__global__ __launch_bounds__(kPrefillThreads, 1) void prefill_kernel(PrefillArgs a) {
     extern __shared__ uint16_t lds[];           // [2][K tile] then [2][V^T tile]
     uint16_t* const k_lds = lds;
     uint16_t* const v_lds = lds + 2 * kKTile;
@@ -113,18 +123,21 @@ __global__ __launch_bounds__(256, 1) void prefill_kernel(PrefillArgs a) {
     const uint16_t* vbase = a.v + (int64_t)b * a.v_stride_b + (int64_t)g * a.v_stride_h;
 
     // Q^T as B operands: column n of block nt is query row q0 + 32 nt + n, step st covers columns 16 st + 8 kb + e
-    uint4 qf[2][8];
-    for (int nt = 0; nt < 2; ++nt) {
-        const int qr = min(q0 + 32 * nt + n, a.seq_len - 1);
+    uint4 qf[8];
+    {
+        const int qr = min(q0 + n, a.seq_len - 1);
         const uint16_t* qrow = qbase + (int64_t)qr * a.q_stride_t;
-        for (int st = 0; st < 8; ++st) qf[nt][st] = *reinterpret_cast<const uint4*>(qrow + 16 * st + 8 * kb);
+#pragma unroll
+        for (int st = 0; st < 8; ++st) qf[st] = *reinterpret_cast<const uint4*>(qrow + 16 * st + 8 * kb);
     }
 
-    f32x16 acc[2][4];
-    for (int nt = 0; nt < 2; ++nt)
-        for (int dt = 0; dt < 4; ++dt)
-            for (int r = 0; r < 16; ++r) acc[nt][dt][r] = 0.f;
-    float m[2] = {-INFINITY, -INFINITY}, l[2] = {0.f, 0.f};
+    f32x16 acc[4];
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[dt][r] = 0.f;
+    float m = -INFINITY, l = 0.f;
+    const int qrow = q0 + n;
 
     const int kv_end = min(qb * kBM + kBM, a.seq_len);        // keys this workgroup needs: [0, kv_end)
     const int n_tiles = (kv_end + kBN - 1) / kBN;
@@ -137,64 +150,58 @@ __global__ __launch_bounds__(256, 1) void prefill_kernel(PrefillArgs a) {
     for (int tile = 0; tile < n_tiles; ++tile) {
         const int buf = tile & 1;
         const bool more = tile + 1 < n_tiles;
-        if (more) load_staging(a, kbase, vbase, (tile + 1) * kBN, stg);
+        // unconditional (the last iteration re-reads its own tile) so that the staging registers have one definition
+        load_staging(a, kbase, vbase, (more ? tile + 1 : tile) * kBN, stg);
 
         const uint16_t* ks = k_lds + buf * kKTile;
         const uint16_t* vs = v_lds + buf * kVTile;
-        for (int tt = 0; tt < 2; ++tt) {                      // two 32-token MFMA tiles per LDS tile
+#pragma unroll 1
+        for (int tt = 0; tt < kBN / 32; ++tt) {               // 32-token MFMA tiles of the LDS tile
             const int tok0 = tile * kBN + 32 * tt;
             if (tok0 > q_last) break;                         // entirely above the diagonal for this wavefront
-            // scores S^T[tok, q] for both column blocks; the K operand is read once per step
-            f32x16 sc[2];
-            for (int nt = 0; nt < 2; ++nt)
-                for (int r = 0; r < 16; ++r) sc[nt][r] = 0.f;
+            f32x16 sc;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sc[r] = 0.f;
 #pragma unroll
             for (int st = 0; st < 8; ++st) {
                 const uint4 ka = *reinterpret_cast<const uint4*>(ks + (32 * tt + n) * kKStride + 16 * st + 8 * kb);
-                sc[0] = mfma32(ka, qf[0][st], sc[0]);
-                sc[1] = mfma32(ka, qf[1][st], sc[1]);
+                sc = mfma32(ka, qf[st], sc);
             }
-            uint4 pb[2][2];                                   // P^T operands [column block][k-step]
             const bool diagonal = tok0 + 31 > q0;             // some (token, row) pair of this tile is masked
+            float tmax = -INFINITY;
 #pragma unroll
-            for (int nt = 0; nt < 2; ++nt) {
-                const int qrow = q0 + 32 * nt + n;
-                float tmax = -INFINITY;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    float x = sc[nt][r] * c;
-                    if (diagonal) {
-                        const int tok = tok0 + 8 * (r >> 2) + 4 * kb + (r & 3);
-                        x = (tok <= qrow) ? x : -INFINITY;
-                    }
-                    sc[nt][r] = x;
-                    tmax = fmaxf(tmax, x);
+            for (int r = 0; r < 16; ++r) {
+                float x = sc[r] * c;
+                if (diagonal) {
+                    const int tok = tok0 + 8 * (r >> 2) + 4 * kb + (r & 3);
+                    x = (tok <= qrow) ? x : -INFINITY;
                 }
-                tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-                const float mn = fmaxf(m[nt], tmax);
-                const float ms = (mn == -INFINITY) ? 0.f : mn;       // a row with nothing visible yet
-                if (__builtin_amdgcn_ballot_w64(mn > m[nt]) != 0) {
-                    const float alpha = exp2f(m[nt] - ms);
-                    l[nt] *= alpha;
-                    for (int dt = 0; dt < 4; ++dt) acc[nt][dt] *= alpha;
-                    m[nt] = mn;
-                }
-                float p[16];
-#pragma unroll
-                for (int r = 0; r < 16; ++r) p[r] = exp2f(sc[nt][r] - ms);
-#pragma unroll
-                for (int ks2 = 0; ks2 < 2; ++ks2) {
-                    uint4 w;
-                    w.x = pack_bf16(p[8 * ks2 + 0], p[8 * ks2 + 1]);
-                    w.y = pack_bf16(p[8 * ks2 + 2], p[8 * ks2 + 3]);
-                    w.z = pack_bf16(p[8 * ks2 + 4], p[8 * ks2 + 5]);
-                    w.w = pack_bf16(p[8 * ks2 + 6], p[8 * ks2 + 7]);
-                    pb[nt][ks2] = w;
-                    l[nt] += (bf16_lo(w.x) + bf16_hi(w.x)) + (bf16_lo(w.y) + bf16_hi(w.y)) +
-                             (bf16_lo(w.z) + bf16_hi(w.z)) + (bf16_lo(w.w) + bf16_hi(w.w));
-                }
+                sc[r] = x;
+                tmax = fmaxf(tmax, x);
             }
-            // O^T += V^T P^T; the V^T operand is read once per (column tile, step) and serves both blocks
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+            const float mn = fmaxf(m, tmax);
+            const float ms = (mn == -INFINITY) ? 0.f : mn;           // a row with nothing visible yet
+            if (__builtin_amdgcn_ballot_w64(mn > m) != 0) {
+                const float alpha = exp2f(m - ms);
+                l *= alpha;
+#pragma unroll
+                for (int dt = 0; dt < 4; ++dt) acc[dt] *= alpha;
+                m = mn;
+            }
+            uint4 pb[2];                                      // P^T operands of the two k-steps
+#pragma unroll
+            for (int ks2 = 0; ks2 < 2; ++ks2) {
+                float p[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) p[e] = exp2f(sc[8 * ks2 + e] - ms);
+                uint4 w;
+                w.x = pack_bf16(p[0], p[1]); w.y = pack_bf16(p[2], p[3]);
+                w.z = pack_bf16(p[4], p[5]); w.w = pack_bf16(p[6], p[7]);
+                pb[ks2] = w;
+                // the normaliser sums the rounded weights: one v_dot2 with (1, 1) per packed pair
+                l = pair_sum(w.w, pair_sum(w.z, pair_sum(w.y, pair_sum(w.x, l))));
+            }
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
@@ -202,33 +209,32 @@ __global__ __launch_bounds__(256, 1) void prefill_kernel(PrefillArgs a) {
                     const uint16_t* vp = vs + (32 * dt + n) * kVStride + 32 * tt + 16 * ks2 + 4 * kb;
                     const uint2 lo = *reinterpret_cast<const uint2*>(vp);
                     const uint2 hi = *reinterpret_cast<const uint2*>(vp + 8);
-                    const uint4 va = make_uint4(lo.x, lo.y, hi.x, hi.y);
-                    acc[0][dt] = mfma32(va, pb[0][ks2], acc[0][dt]);
-                    acc[1][dt] = mfma32(va, pb[1][ks2], acc[1][dt]);
+                    acc[dt] = mfma32(make_uint4(lo.x, lo.y, hi.x, hi.y), pb[ks2], acc[dt]);
                 }
         }
         if (more) store_staging(stg, k_lds + (buf ^ 1) * kKTile, v_lds + (buf ^ 1) * kVTile);
         __syncthreads();
     }
 
-    // epilogue: normalise and store; lane holds query row q0 + 32 nt + n, columns 32 dt + 8 (r/4) + 4 kb + r%4
-    for (int nt = 0; nt < 2; ++nt) {
-        float lt = l[nt];
+    // epilogue: normalise and store; lane holds query row q0 + n, columns 32 dt + 8 (r/4) + 4 kb + r%4
+    {
+        float lt = l;
         lt += __shfl_xor(lt, 32);
-        const int qrow = q0 + 32 * nt + n;
         if (qrow < a.seq_len) {
             const float inv = lt > 0.f ? 1.f / lt : 0.f;
             float* orow = a.out + (int64_t)b * a.o_stride_b + (int64_t)qrow * a.o_stride_t + (int64_t)h * a.o_stride_h;
+#pragma unroll
             for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
                     float4 o;
-                    o.x = acc[nt][dt][4 * r4 + 0] * inv; o.y = acc[nt][dt][4 * r4 + 1] * inv;
-                    o.z = acc[nt][dt][4 * r4 + 2] * inv; o.w = acc[nt][dt][4 * r4 + 3] * inv;
+                    o.x = acc[dt][4 * r4 + 0] * inv; o.y = acc[dt][4 * r4 + 1] * inv;
+                    o.z = acc[dt][4 * r4 + 2] * inv; o.w = acc[dt][4 * r4 + 3] * inv;
                     *reinterpret_cast<float4*>(orow + 32 * dt + 8 * r4 + 4 * kb) = o;
                 }
             if (a.lse != nullptr && kb == 0)
                 a.lse[((int64_t)b * a.seq_len + qrow) * a.num_q_heads + h] =
-                    lt > 0.f ? 0.6931471805599453f * (m[nt] + log2f(lt)) : -INFINITY;
+                    lt > 0.f ? 0.6931471805599453f * (m + log2f(lt)) : -INFINITY;
         }
     }
 }
@@ -247,7 +253,7 @@ hipError_t launch_prefill(const PrefillArgs& a, hipStream_t s) {
     const int n_qb = (a.seq_len + kBM - 1) / kBM;
     const int heads_per_xcd = (a.num_kv_heads + 7) / 8;
     const int64_t grid = 8LL * a.group * n_qb * heads_per_xcd * a.batch;
-    hipLaunchKernelGGL(prefill_kernel, dim3((unsigned)grid), dim3(256), kPrefillLds, s, a);
+    hipLaunchKernelGGL(prefill_kernel, dim3((unsigned)grid), dim3(kPrefillThreads), kPrefillLds, s, a);
     return hipGetLastError();
 }
 
