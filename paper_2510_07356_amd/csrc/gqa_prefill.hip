@@ -116,7 +116,8 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_kernel(PrefillArgs
     const int n = lane & 31, kb = lane >> 5;
     const int q0 = qb * kBM + wave * kWaveRows;              // first query row of this wavefront
     const int q_last = min(q0 + kWaveRows, a.seq_len) - 1;   // may be < q0: wavefront without rows
-    const float c = a.scale_log2e;
+    const float c = fabsf(a.scale_log2e);                    // a negative scale is applied by negating Q (exact)
+    const uint32_t qsign = a.scale_log2e < 0.f ? 0x80008000u : 0u;
 
     const uint16_t* qbase = a.q + (int64_t)b * a.q_stride_b + (int64_t)h * a.q_stride_h;
     const uint16_t* kbase = a.k + (int64_t)b * a.k_stride_b + (int64_t)g * a.k_stride_h;
@@ -128,7 +129,11 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_kernel(PrefillArgs
         const int qr = min(q0 + n, a.seq_len - 1);
         const uint16_t* qrow = qbase + (int64_t)qr * a.q_stride_t;
 #pragma unroll
-        for (int st = 0; st < 8; ++st) qf[st] = *reinterpret_cast<const uint4*>(qrow + 16 * st + 8 * kb);
+        for (int st = 0; st < 8; ++st) {
+            uint4 x = *reinterpret_cast<const uint4*>(qrow + 16 * st + 8 * kb);
+            x.x ^= qsign; x.y ^= qsign; x.z ^= qsign; x.w ^= qsign;
+            qf[st] = x;
+        }
     }
 
     f32x16 acc[4];
@@ -136,7 +141,7 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_kernel(PrefillArgs
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[dt][r] = 0.f;
-    float m = -INFINITY, l = 0.f;
+    float m = -INFINITY, l = 0.f;          // running maximum of the raw scores (times |scale| log2 e in the exponent)
     const int qrow = q0 + n;
 
     const int kv_end = min(qb * kBM + kBM, a.seq_len);        // keys this workgroup needs: [0, kv_end)
@@ -167,34 +172,44 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_kernel(PrefillArgs
                 const uint4 ka = *reinterpret_cast<const uint4*>(ks + (32 * tt + n) * kKStride + 16 * st + 8 * kb);
                 sc = mfma32(ka, qf[st], sc);
             }
+            // online softmax on the raw scores (the scale is folded into the exponent: 2^(s c - m c));
+            // only tiles that touch the diagonal pay for the mask
             const bool diagonal = tok0 + 31 > q0;             // some (token, row) pair of this tile is masked
-            float tmax = -INFINITY;
+            uint32_t visible = 0xffffu;                       // bit r: register r holds a visible token
+            if (diagonal) {
+                visible = 0;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                float x = sc[r] * c;
-                if (diagonal) {
-                    const int tok = tok0 + 8 * (r >> 2) + 4 * kb + (r & 3);
-                    x = (tok <= qrow) ? x : -INFINITY;
-                }
-                sc[r] = x;
-                tmax = fmaxf(tmax, x);
+                for (int r = 0; r < 16; ++r)
+                    if (tok0 + 8 * (r >> 2) + 4 * kb + (r & 3) <= qrow) visible |= 1u << r;
+            }
+            float tmax = -INFINITY;
+            if (diagonal) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, (visible >> r) & 1u ? sc[r] : -INFINITY);
+            } else {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, sc[r]);
             }
             tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-            const float mn = fmaxf(m, tmax);
-            const float ms = (mn == -INFINITY) ? 0.f : mn;           // a row with nothing visible yet
+            const float mn = fmaxf(m, tmax);                  // finite: token 0 is visible to every row
             if (__builtin_amdgcn_ballot_w64(mn > m) != 0) {
-                const float alpha = exp2f(m - ms);
+                const float alpha = __builtin_amdgcn_exp2f((m - mn) * c);   // first tile: 2^(-inf) = 0
                 l *= alpha;
 #pragma unroll
                 for (int dt = 0; dt < 4; ++dt) acc[dt] *= alpha;
                 m = mn;
             }
+            const float mc = -m * c;
             uint4 pb[2];                                      // P^T operands of the two k-steps
 #pragma unroll
             for (int ks2 = 0; ks2 < 2; ++ks2) {
                 float p[8];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) p[e] = exp2f(sc[8 * ks2 + e] - ms);
+                for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(fmaf(sc[8 * ks2 + e], c, mc));
+                if (diagonal) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) p[e] = (visible >> (8 * ks2 + e)) & 1u ? p[e] : 0.f;
+                }
                 uint4 w;
                 w.x = pack_bf16(p[0], p[1]); w.y = pack_bf16(p[2], p[3]);
                 w.z = pack_bf16(p[4], p[5]); w.w = pack_bf16(p[6], p[7]);
@@ -234,7 +249,7 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_kernel(PrefillArgs
                 }
             if (a.lse != nullptr && kb == 0)
                 a.lse[((int64_t)b * a.seq_len + qrow) * a.num_q_heads + h] =
-                    lt > 0.f ? 0.6931471805599453f * (m + log2f(lt)) : -INFINITY;
+                    lt > 0.f ? 0.6931471805599453f * (m * c + log2f(lt)) : -INFINITY;
         }
     }
 }
