@@ -471,3 +471,92 @@ def run_workload(w, dev=None, chunk_tokens: int = 0, kernel_variant: int = 0, us
     ms = gqa_decode_attn(params, q, k, v, dev["kv_lens"], dev["block_table"],
                          w.kv_lens if use_host_lens else None, out, lse, ws, timed=timed)
     return (out, lse, ms) if timed else (out, lse)
+
+
+# ---------------------------------------------------------------------------
+# Host-only metrics and curation rules of the paper (include/concur_curation.h)
+# ---------------------------------------------------------------------------
+CURATION_EXPORTS = ("concur_speedup", "concur_fast_p", "concur_exec_pass_at_k", "concur_fast1_pass_at_k",
+                    "concur_arl", "concur_difficulty_bins", "concur_select")
+
+
+def _np(a, dtype):
+    import numpy as np
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def _setup_curation():
+    d, i64, vp = ctypes.c_double, ctypes.c_int64, ctypes.c_void_p
+    _lib.concur_speedup.restype = ctypes.c_int
+    _lib.concur_speedup.argtypes = [i64, vp, vp, vp, vp]
+    _lib.concur_fast_p.restype = d
+    _lib.concur_fast_p.argtypes = [i64, vp, d]
+    _lib.concur_exec_pass_at_k.restype = d
+    _lib.concur_exec_pass_at_k.argtypes = [i64, ctypes.c_int32, vp]
+    _lib.concur_fast1_pass_at_k.restype = d
+    _lib.concur_fast1_pass_at_k.argtypes = [i64, ctypes.c_int32, vp]
+    _lib.concur_arl.restype = d
+    _lib.concur_arl.argtypes = [i64, ctypes.c_int32, vp]
+    _lib.concur_difficulty_bins.restype = ctypes.c_int
+    _lib.concur_difficulty_bins.argtypes = [i64, vp, d, d, vp]
+    _lib.concur_select.restype = i64
+    _lib.concur_select.argtypes = [i64, vp, vp, vp, vp, d, i64, vp, vp]
+
+
+_setup_curation()
+
+
+def concur_speedup(t_torch, t_kernel, correct):
+    import numpy as np
+    tt, tk, c = _np(t_torch, np.float64), _np(t_kernel, np.float64), _np(correct, np.uint8)
+    out = np.empty(len(tt), dtype=np.float64)
+    if _lib.concur_speedup(len(tt), tt.ctypes.data, tk.ctypes.data, c.ctypes.data, out.ctypes.data) != 0:
+        raise ValueError("concur_speedup: bad arguments")
+    return out
+
+
+def concur_fast_p(speedup, p):
+    import numpy as np
+    s = _np(speedup, np.float64)
+    return float(_lib.concur_fast_p(len(s), s.ctypes.data, float(p)))
+
+
+def concur_exec_pass_at_k(correct_rows):
+    import numpy as np
+    c = _np(correct_rows, np.uint8)
+    return float(_lib.concur_exec_pass_at_k(c.shape[0], c.shape[1], c.ctypes.data))
+
+
+def concur_fast1_pass_at_k(speedup_rows):
+    import numpy as np
+    s = _np(speedup_rows, np.float64)
+    return float(_lib.concur_fast1_pass_at_k(s.shape[0], s.shape[1], s.ctypes.data))
+
+
+def concur_arl(length_rows):
+    import numpy as np
+    L = _np(length_rows, np.int32)
+    return float(_lib.concur_arl(L.shape[0], L.shape[1], L.ctypes.data))
+
+
+def concur_difficulty_bins(task_arl, lo=4000.0, hi=8500.0):
+    import numpy as np
+    a = _np(task_arl, np.float64)
+    out = np.empty(len(a), dtype=np.int32)
+    if _lib.concur_difficulty_bins(len(a), a.ctypes.data, float(lo), float(hi), out.ctypes.data) != 0:
+        raise ValueError("concur_difficulty_bins: bad arguments")
+    return out
+
+
+def concur_select(task_id, speedup, reasoning_len, single_op, threshold=5.0, quota=544):
+    """Returns (flags uint8 per record, counts (a, b-only, c))."""
+    import numpy as np
+    t, s = _np(task_id, np.int64), _np(speedup, np.float64)
+    r, o = _np(reasoning_len, np.int32), _np(single_op, np.uint8)
+    flags = np.empty(len(t), dtype=np.uint8)
+    counts = np.zeros(3, dtype=np.int64)
+    rc = _lib.concur_select(len(t), t.ctypes.data, s.ctypes.data, r.ctypes.data, o.ctypes.data, float(threshold),
+                            int(quota), flags.ctypes.data, counts.ctypes.data)
+    if rc < 0:
+        raise ValueError("concur_select: bad arguments")
+    return flags, tuple(int(x) for x in counts)

@@ -34,6 +34,15 @@ def test_header_and_library_agree(lib):
         assert hasattr(raw, n), n
 
 
+def test_curation_header_and_library_agree(lib):
+    text = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "concur_curation.h")).read(), flags=re.S)
+    names = sorted(set(re.findall(r"\b(concur_\w+)\s*\(", text)))
+    assert set(names) == set(lib.CURATION_EXPORTS) and len(names) == 7
+    raw = ctypes.CDLL(LIB)
+    for n in names:
+        assert hasattr(raw, n), n
+
+
 def test_version_and_strerror(lib):
     assert lib.gqa_decode_version() >= 100
     assert lib.gqa_decode_strerror(0) == "ok"
