@@ -154,7 +154,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", type=int, default=0, metavar="MIB",
                     help="also run the plain copy kernel over this many MiB, three times (counter scaling in profiles)")
-    ap.add_argument("--stream-read", action="store_true", help="also time the streaming-read probe over one cache copy")
+    ap.add_argument("--no-stream-read", action="store_true", help="skip the streaming-read probe over one cache copy")
     ap.add_argument("--shared-prefix", action="store_true",
                     help="benchmark the shared-prefix entry point on a tasks x samples batch instead")
     ap.add_argument("--prefill", action="store_true", help="benchmark causal prefill attention instead")
@@ -248,6 +248,8 @@ def main() -> int:
         },
         "pct_of_hbm_peak": round(100.0 * value * 1e3 / HBM_PEAK_GBPS, 2),
         "sequences_per_s": round(w.batch / (ms_per_step * 1e-3), 1),
+        # derived: attention-only bound on generated tokens/s if a 64-layer model made this call per layer
+        "derived_tokens_per_s_64_layers": round(w.batch / (64 * ms_per_step * 1e-3), 1),
         "ms_per_step_without_event_records": round(ms_plain, 5),
         "kernel_ms": {"partial": round(partial_avg_ms, 5),
                       "combine": round(combine_ms / n_timed, 5), "launches_timed": n_timed},
@@ -272,7 +274,7 @@ def main() -> int:
         torch.cuda.synchronize()
         result["calibration_copy_bytes"] = n
         del src, dst
-    if args.stream_read:
+    if not args.no_stream_read:
         kflat = devs[0]["k"].untyped_storage()
         src = torch.empty(0, dtype=torch.uint8, device="cuda:0").set_(kflat)
         sink = torch.empty(1 << 16, dtype=torch.int32, device="cuda:0")
@@ -284,7 +286,9 @@ def main() -> int:
             ev1.record()
             ev1.synchronize()
             best = min(best, ev0.elapsed_time(ev1))
-        result["stream_read_probe_GBps"] = round(src.numel() / best / 1e6, 1)
+        ceiling = src.numel() / best / 1e6
+        result["stream_read_probe_GBps"] = round(ceiling, 1)
+        result["pct_of_stream_read_probe"] = round(100.0 * value * 1e3 / ceiling, 2)
 
     if not args.no_cpu_baseline:
         from oracle import decode_attn
@@ -295,6 +299,9 @@ def main() -> int:
             t_cpu_total += time.perf_counter() - t3
             reps += 1
         t_cpu = t_cpu_total / reps
+        t4 = time.perf_counter()
+        decode_attn(w.q, w.k, w.v, w.kv_lens, w.scale, block_table=w.block_table, page_size=w.page_size, threads=1)
+        t_one = time.perf_counter() - t4
         calls[0]()
         torch.cuda.synchronize()
         err = out.double().cpu().numpy() - ref.out
@@ -304,7 +311,8 @@ def main() -> int:
             "cores": ref.threads,
             "kind": "oracle",
             "sample": f"the whole workload ({w.batch} sequences, {w.kv_tokens} KV tokens), mean of {reps} runs, "
-                      f"{t_cpu:.3f} s wall each on {ref.threads} threads",
+                      f"{t_cpu:.3f} s wall each on {ref.threads} threads; one run on a single thread: {t_one:.2f} s",
+            "single_thread_value": round(kv_bytes / t_one / 1e12, 6),
         }
         result["parity"] = {"max_abs": float(np.abs(err).max()),
                             "rel_l2": float(np.linalg.norm(err) / np.linalg.norm(ref.out))}
