@@ -55,6 +55,14 @@ __device__ __forceinline__ float pair_sum(uint32_t pair, float acc) {
                                            acc, false);
 }
 
+// max of a value and the one held by lane ^ 32: v_permlane32_swap exchanges the upper half of its first
+// operand with the lower half of its second, so both results hold one half broadcast to both halves
+__device__ __forceinline__ float max_across_halves(float x) {
+    const unsigned u = __builtin_bit_cast(unsigned, x);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return fmaxf(__builtin_bit_cast(float, (unsigned)r[0]), __builtin_bit_cast(float, (unsigned)r[1]));
+}
+
 struct Staging {          // one K/V tile on its way from global memory to LDS (per thread)
     uint4 k[4];           // token (tid / 16) + 32 i, 16-byte piece tid % 16
     uint4 v[4];           // tokens 4 * (tid / 16) + i, 16-byte piece tid % 16
@@ -95,9 +103,9 @@ __device__ __forceinline__ void store_staging(const Staging& st, uint16_t* ks, u
 }
 
 __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_kernel(PrefillArgs a) {
-    extern __shared__ uint16_t lds[];           // [2][K tile] then [2][V^T tile]
-    uint16_t* const k_lds = lds;
-    uint16_t* const v_lds = lds + 2 * kKTile;
+    extern __shared__ uint16_t lds[];           // [2][V^T tile] then [2][K tile]
+    uint16_t* const v_lds = lds;                // V^T first: its read offsets then fit the 16-bit immediates
+    uint16_t* const k_lds = lds + 2 * kVTile;
 
     // task: XCD x serves KV heads x, x + 8, ...; row blocks from the last to the first
     const int G = a.group;
@@ -112,7 +120,7 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_kernel(PrefillArgs
     if (g >= a.num_kv_heads) return;
     const int h = g * G + hh;
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n = lane & 31, kb = lane >> 5;
     const int q0 = qb * kBM + wave * kWaveRows;              // first query row of this wavefront
     const int q_last = min(q0 + kWaveRows, a.seq_len) - 1;   // may be < q0: wavefront without rows
@@ -190,7 +198,7 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_kernel(PrefillArgs
 #pragma unroll
                 for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, sc[r]);
             }
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+            tmax = max_across_halves(tmax);
             const float mn = fmaxf(m, tmax);                  // finite: token 0 is visible to every row
             if (__builtin_amdgcn_ballot_w64(mn > m) != 0) {
                 const float alpha = __builtin_amdgcn_exp2f((m - mn) * c);   // first tile: 2^(-inf) = 0
