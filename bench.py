@@ -26,10 +26,13 @@ HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published peak
 EVENT_STRIDE = 4            # one step in four records HIP events around its kernels
 
 
+PARTIAL_KERNEL_SOURCES = ("gqa_api.hip", "gqa_internal.h", "gqa_mfma_tile.h", "gqa_partial_mfma.hip")
+
+
 def measured_traffic(config_index: int):
     """HBM bytes per launch of the partial kernel from the committed counter summary, or None when
-    the kernel sources have changed since the counters were taken."""
-    import glob
+    the sources the kernel is built from (its own file, the tile primitives, the shared declarations
+    and the launch code) have changed since the counters were taken."""
     import hashlib
     path = os.path.join(ROOT, "profiles", "partial_mfma_kernel_hbm_traffic.txt")
     if not os.path.exists(path):
@@ -40,9 +43,9 @@ def measured_traffic(config_index: int):
             k, v = line.split("=", 1)
             kv[k.strip()] = v.strip()
     h = hashlib.sha256()
-    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2510_07356_amd", "csrc", "*"))):
-        h.update(os.path.basename(f).encode())
-        h.update(open(f, "rb").read())
+    for name in PARTIAL_KERNEL_SOURCES:
+        h.update(name.encode())
+        h.update(open(os.path.join(ROOT, "paper_2510_07356_amd", "csrc", name), "rb").read())
     if kv.get("source_sha256") != h.hexdigest():
         return None
     v = kv.get(f"config{config_index}_partial_traffic_bytes")

@@ -5,12 +5,18 @@
 // through the same attention (Section 4.1 of the paper).  Row t of the result is by definition
 // the decode attention of query t over the first t + 1 keys.
 //
-// Decomposition.  One workgroup (8 wavefronts, two per SIMD so that one wavefront's exponentials
-// overlap the other's matrix products) owns 256 consecutive query rows of one query head, 32 rows
-// per wavefront, and walks the key/value tokens 0 .. (last row) in tiles of 128.  A K tile is staged
-// in LDS row-major, a V tile transposed ([column][token], transposed in registers with v_perm_b32
-// on the way in), both double-buffered: the global loads of tile j+1 are issued before the compute
-// on tile j and written to the other buffer after it, one barrier per tile.
+// Decomposition.  One workgroup (8 wavefronts, two per SIMD) owns 256 consecutive query rows of one
+// query head, 32 rows per wavefront, and walks the key/value tokens 0 .. (last row) in tiles of 128.
+// A K tile is staged in LDS row-major, a V tile transposed ([column][token], transposed in registers
+// with v_perm_b32 on the way in; inside a V^T row the 4-token groups of column block dt sit at
+// position group ^ 2 dt, which makes the transposed 8-byte stores bank-conflict free), both
+// double-buffered with one barrier per tile.  The two halves of the next tile travel in turn, so
+// that only one of them holds registers: K is requested at the start of a tile and stored after its
+// second 32-token step, V is requested then and stored at the end.
+//
+// LDS fragments are requested ahead of the matrix instructions that use them: the V^T fragments of
+// a 32-token step and the K fragments of the next step are requested right after the step's score
+// products, so their latency passes behind the softmax.
 //
 // Per wavefront and 32 tokens (v_mfma_f32_32x32x16_bf16; lane l: n = l % 32, kb = l / 32;
 // A[m][8kb+e], B[8kb+e][n], D[8(r/4) + 4kb + r%4][n] in register r):
@@ -63,49 +69,85 @@ __device__ __forceinline__ float max_across_halves(float x) {
     return fmaxf(__builtin_bit_cast(float, (unsigned)r[0]), __builtin_bit_cast(float, (unsigned)r[1]));
 }
 
-struct Staging {          // one K/V tile on its way from global memory to LDS (per thread)
-    uint4 k[4];           // token (tid / 16) + 32 i, 16-byte piece tid % 16
-    uint4 v[4];           // tokens 4 * (tid / 16) + i, 16-byte piece tid % 16
-};
+// One K (V) tile on its way from global memory to LDS, per thread.  The two halves are staged in
+// turn so that only one of them occupies registers at a time: K of the next tile travels during the
+// first half of the work on the current tile, V during the second.
+struct StagingK { uint4 r0, r1, r2, r3; };   // token (tid / 16) + 32 i, 16-byte piece tid % 16
+struct StagingV { uint4 r0, r1, r2, r3; };   // tokens 4 * (tid / 16) + i, 16-byte piece tid % 16
 
-__device__ __forceinline__ void load_staging(const PrefillArgs& a, const uint16_t* kbase, const uint16_t* vbase,
-                                             int tok0, Staging& st) {
+__device__ __forceinline__ void load_k_tile(const PrefillArgs& a, const uint16_t* kbase, int tok0, StagingK& st) {
     const int tid = threadIdx.x;
     const int piece = tid & 15, grp = tid >> 4;
-    const int last = a.seq_len - 1;
-    for (int i = 0; i < 4; ++i) {
-        const int tk = min(tok0 + grp + 32 * i, last);                  // rows beyond the sequence re-read the last row
-        st.k[i] = *reinterpret_cast<const uint4*>(kbase + (int64_t)tk * a.k_stride_t + 8 * piece);
-        const int tv = min(tok0 + 4 * grp + i, last);
-        st.v[i] = *reinterpret_cast<const uint4*>(vbase + (int64_t)tv * a.v_stride_t + 8 * piece);
+    if (tok0 + kBN <= a.seq_len) {
+        // whole tile inside the sequence: one per-thread pointer, wave-uniform row offsets
+        const uint16_t* kp = kbase + (int64_t)tok0 * a.k_stride_t + ((int64_t)grp * a.k_stride_t + 8 * piece);
+        const int64_t k32 = 32 * a.k_stride_t;
+        st.r0 = *reinterpret_cast<const uint4*>(kp);
+        st.r1 = *reinterpret_cast<const uint4*>(kp + k32);
+        st.r2 = *reinterpret_cast<const uint4*>(kp + 2 * k32);
+        st.r3 = *reinterpret_cast<const uint4*>(kp + 3 * k32);
+    } else {
+        const int last = a.seq_len - 1;                 // rows beyond the sequence re-read the last row
+        auto row = [&](int i) {
+            return *reinterpret_cast<const uint4*>(kbase + (int64_t)min(tok0 + grp + 32 * i, last) * a.k_stride_t + 8 * piece);
+        };
+        st.r0 = row(0); st.r1 = row(1); st.r2 = row(2); st.r3 = row(3);
     }
 }
 
-__device__ __forceinline__ void store_staging(const Staging& st, uint16_t* ks, uint16_t* vs) {
+__device__ __forceinline__ void load_v_tile(const PrefillArgs& a, const uint16_t* vbase, int tok0, StagingV& st) {
     const int tid = threadIdx.x;
     const int piece = tid & 15, grp = tid >> 4;
-    for (int i = 0; i < 4; ++i)
-        *reinterpret_cast<uint4*>(ks + (grp + 32 * i) * kKStride + 8 * piece) = st.k[i];
-    // 4 tokens x 8 columns -> 8 columns x 4 tokens, then one 8-byte store per column
+    if (tok0 + kBN <= a.seq_len) {
+        const uint16_t* vp = vbase + (int64_t)tok0 * a.v_stride_t + ((int64_t)(4 * grp) * a.v_stride_t + 8 * piece);
+        st.r0 = *reinterpret_cast<const uint4*>(vp);
+        st.r1 = *reinterpret_cast<const uint4*>(vp + a.v_stride_t);
+        st.r2 = *reinterpret_cast<const uint4*>(vp + 2 * a.v_stride_t);
+        st.r3 = *reinterpret_cast<const uint4*>(vp + 3 * a.v_stride_t);
+    } else {
+        const int last = a.seq_len - 1;
+        auto row = [&](int i) {
+            return *reinterpret_cast<const uint4*>(vbase + (int64_t)min(tok0 + 4 * grp + i, last) * a.v_stride_t + 8 * piece);
+        };
+        st.r0 = row(0); st.r1 = row(1); st.r2 = row(2); st.r3 = row(3);
+    }
+}
+
+__device__ __forceinline__ void store_k_tile(const StagingK& st, uint16_t* ks) {
+    const int tid = threadIdx.x;
+    const int piece = tid & 15, grp = tid >> 4;
+    *reinterpret_cast<uint4*>(ks + (grp + 0) * kKStride + 8 * piece) = st.r0;
+    *reinterpret_cast<uint4*>(ks + (grp + 32) * kKStride + 8 * piece) = st.r1;
+    *reinterpret_cast<uint4*>(ks + (grp + 64) * kKStride + 8 * piece) = st.r2;
+    *reinterpret_cast<uint4*>(ks + (grp + 96) * kKStride + 8 * piece) = st.r3;
+}
+
+__device__ __forceinline__ void store_v_tile(const StagingV& st, uint16_t* vs) {
+    const int tid = threadIdx.x;
+    const int piece = tid & 15, grp = tid >> 4;
+    // 4 tokens x 8 columns -> 8 columns x 4 tokens, then one 8-byte store per column.  Within a V^T row
+    // the 4-token groups of column block dt = column / 32 sit at position group ^ 2 dt: the 16 column
+    // pieces a wavefront writes at once then fall into distinct banks.
+    const int slot = grp ^ (2 * (piece >> 2));
     auto column_pair = [&](uint32_t t0, uint32_t t1, uint32_t t2, uint32_t t3, int pr) {
         uint2 even, odd;                                                  // columns 2 pr and 2 pr + 1, tokens 0..3
         even.x = __builtin_amdgcn_perm(t1, t0, 0x05040100u);
         even.y = __builtin_amdgcn_perm(t3, t2, 0x05040100u);
         odd.x = __builtin_amdgcn_perm(t1, t0, 0x07060302u);
         odd.y = __builtin_amdgcn_perm(t3, t2, 0x07060302u);
-        *reinterpret_cast<uint2*>(vs + (8 * piece + 2 * pr) * kVStride + 4 * grp) = even;
-        *reinterpret_cast<uint2*>(vs + (8 * piece + 2 * pr + 1) * kVStride + 4 * grp) = odd;
+        *reinterpret_cast<uint2*>(vs + (8 * piece + 2 * pr) * kVStride + 4 * slot) = even;
+        *reinterpret_cast<uint2*>(vs + (8 * piece + 2 * pr + 1) * kVStride + 4 * slot) = odd;
     };
-    column_pair(st.v[0].x, st.v[1].x, st.v[2].x, st.v[3].x, 0);
-    column_pair(st.v[0].y, st.v[1].y, st.v[2].y, st.v[3].y, 1);
-    column_pair(st.v[0].z, st.v[1].z, st.v[2].z, st.v[3].z, 2);
-    column_pair(st.v[0].w, st.v[1].w, st.v[2].w, st.v[3].w, 3);
+    column_pair(st.r0.x, st.r1.x, st.r2.x, st.r3.x, 0);
+    column_pair(st.r0.y, st.r1.y, st.r2.y, st.r3.y, 1);
+    column_pair(st.r0.z, st.r1.z, st.r2.z, st.r3.z, 2);
+    column_pair(st.r0.w, st.r1.w, st.r2.w, st.r3.w, 3);
 }
 
-__global__ __launch_bounds__(kPrefillThreads, 1) void prefill_kernel(PrefillArgs a) {
-    extern __shared__ uint16_t lds[];           // [2][V^T tile] then [2][K tile]
-    uint16_t* const v_lds = lds;                // V^T first: its read offsets then fit the 16-bit immediates
-    uint16_t* const k_lds = lds + 2 * kVTile;
+__global__ __launch_bounds__(kPrefillThreads, 1) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefill_kernel(PrefillArgs a) {
+    extern __shared__ uint16_t lds[];           // [2][K tile] then [2][V^T tile]
+    uint16_t* const k_lds = lds;
+    uint16_t* const v_lds = lds + 2 * kKTile;
 
     // task: XCD x serves KV heads x, x + 8, ...; row blocks from the last to the first
     const int G = a.group;
@@ -155,49 +197,70 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_kernel(PrefillArgs
     const int kv_end = min(qb * kBM + kBM, a.seq_len);        // keys this workgroup needs: [0, kv_end)
     const int n_tiles = (kv_end + kBN - 1) / kBN;
 
-    Staging stg;
-    load_staging(a, kbase, vbase, 0, stg);
-    store_staging(stg, k_lds, v_lds);
+    {
+        StagingK k0;
+        StagingV v0;
+        load_k_tile(a, kbase, 0, k0);
+        load_v_tile(a, vbase, 0, v0);
+        store_k_tile(k0, k_lds);
+        store_v_tile(v0, v_lds);
+    }
     __syncthreads();
 
     for (int tile = 0; tile < n_tiles; ++tile) {
         const int buf = tile & 1;
         const bool more = tile + 1 < n_tiles;
-        // unconditional (the last iteration re-reads its own tile) so that the staging registers have one definition
-        load_staging(a, kbase, vbase, (more ? tile + 1 : tile) * kBN, stg);
+        const int next_tok = (more ? tile + 1 : tile) * kBN;   // the last iteration re-reads its own tile (never stored)
+        StagingK stk;
+        load_k_tile(a, kbase, next_tok, stk);
 
         const uint16_t* ks = k_lds + buf * kKTile;
         const uint16_t* vs = v_lds + buf * kVTile;
-#pragma unroll 1
-        for (int tt = 0; tt < kBN / 32; ++tt) {               // 32-token MFMA tiles of the LDS tile
+        // K fragments of the first 32-token tile; afterwards they are requested one tile ahead
+        uint4 kf[8];
+#pragma unroll
+        for (int st = 0; st < 8; ++st)
+            kf[st] = *reinterpret_cast<const uint4*>(ks + n * kKStride + 16 * st + 8 * kb);
+        // one 32-token step; false once the step lies entirely above the diagonal for this wavefront
+        auto step = [&](int tt) -> bool {
             const int tok0 = tile * kBN + 32 * tt;
-            if (tok0 > q_last) break;                         // entirely above the diagonal for this wavefront
+            if (tok0 > q_last) return false;
             f32x16 sc;
 #pragma unroll
             for (int r = 0; r < 16; ++r) sc[r] = 0.f;
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int st = 0; st < 8; ++st) {
-                const uint4 ka = *reinterpret_cast<const uint4*>(ks + (32 * tt + n) * kKStride + 16 * st + 8 * kb);
-                sc = mfma32(ka, qf[st], sc);
+            for (int st = 0; st < 8; ++st) sc = mfma32(kf[st], qf[st], sc);
+            __builtin_amdgcn_sched_barrier(0);
+            // requests that do not depend on the softmax: V^T of this tile, K of the next one
+            uint2 vf[16];
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                for (int ks2 = 0; ks2 < 2; ++ks2) {
+                    const uint16_t* vp = vs + (32 * dt + n) * kVStride + 32 * tt + 4 * (((4 * ks2) ^ (2 * dt)) + kb);
+                    vf[4 * dt + 2 * ks2] = *reinterpret_cast<const uint2*>(vp);
+                    vf[4 * dt + 2 * ks2 + 1] = *reinterpret_cast<const uint2*>(vp + ((dt & 1) ? -8 : 8));
+                }
+            {
+                const int tn = min(tt + 1, kBN / 32 - 1);
+#pragma unroll
+                for (int st = 0; st < 8; ++st)
+                    kf[st] = *reinterpret_cast<const uint4*>(ks + (32 * tn + n) * kKStride + 16 * st + 8 * kb);
             }
+            __builtin_amdgcn_sched_barrier(0);
             // online softmax on the raw scores (the scale is folded into the exponent: 2^(s c - m c));
             // only tiles that touch the diagonal pay for the mask
             const bool diagonal = tok0 + 31 > q0;             // some (token, row) pair of this tile is masked
-            uint32_t visible = 0xffffu;                       // bit r: register r holds a visible token
+            const int ahead = tok0 + 4 * kb - qrow;           // register r holds token qrow + ahead + 8 (r / 4) + r % 4
             if (diagonal) {
-                visible = 0;
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
-                    if (tok0 + 8 * (r >> 2) + 4 * kb + (r & 3) <= qrow) visible |= 1u << r;
+                    if (ahead + 8 * (r >> 2) + (r & 3) > 0) sc[r] = -INFINITY;
             }
-            float tmax = -INFINITY;
-            if (diagonal) {
+            float tmax = sc[0];
 #pragma unroll
-                for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, (visible >> r) & 1u ? sc[r] : -INFINITY);
-            } else {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, sc[r]);
-            }
+            for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, sc[r]);
             tmax = max_across_halves(tmax);
             const float mn = fmaxf(m, tmax);                  // finite: token 0 is visible to every row
             if (__builtin_amdgcn_ballot_w64(mn > m) != 0) {
@@ -208,34 +271,43 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_kernel(PrefillArgs
                 m = mn;
             }
             const float mc = -m * c;
+            float p[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) p[r] = __builtin_amdgcn_exp2f(fmaf(sc[r], c, mc));
+            if (diagonal) {                                   // also covers a zero scale, where -inf * 0 is not a number
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (ahead + 8 * (r >> 2) + (r & 3) > 0) p[r] = 0.f;
+            }
             uint4 pb[2];                                      // P^T operands of the two k-steps
 #pragma unroll
             for (int ks2 = 0; ks2 < 2; ++ks2) {
-                float p[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(fmaf(sc[8 * ks2 + e], c, mc));
-                if (diagonal) {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) p[e] = (visible >> (8 * ks2 + e)) & 1u ? p[e] : 0.f;
-                }
                 uint4 w;
-                w.x = pack_bf16(p[0], p[1]); w.y = pack_bf16(p[2], p[3]);
-                w.z = pack_bf16(p[4], p[5]); w.w = pack_bf16(p[6], p[7]);
+                w.x = pack_bf16(p[8 * ks2 + 0], p[8 * ks2 + 1]); w.y = pack_bf16(p[8 * ks2 + 2], p[8 * ks2 + 3]);
+                w.z = pack_bf16(p[8 * ks2 + 4], p[8 * ks2 + 5]); w.w = pack_bf16(p[8 * ks2 + 6], p[8 * ks2 + 7]);
                 pb[ks2] = w;
                 // the normaliser sums the rounded weights: one v_dot2 with (1, 1) per packed pair
                 l = pair_sum(w.w, pair_sum(w.z, pair_sum(w.y, pair_sum(w.x, l))));
             }
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
                 for (int ks2 = 0; ks2 < 2; ++ks2) {
-                    const uint16_t* vp = vs + (32 * dt + n) * kVStride + 32 * tt + 16 * ks2 + 4 * kb;
-                    const uint2 lo = *reinterpret_cast<const uint2*>(vp);
-                    const uint2 hi = *reinterpret_cast<const uint2*>(vp + 8);
+                    const uint2 lo = vf[4 * dt + 2 * ks2], hi = vf[4 * dt + 2 * ks2 + 1];
                     acc[dt] = mfma32(make_uint4(lo.x, lo.y, hi.x, hi.y), pb[ks2], acc[dt]);
                 }
-        }
-        if (more) store_staging(stg, k_lds + (buf ^ 1) * kKTile, v_lds + (buf ^ 1) * kVTile);
+            return true;
+        };
+        bool live = true;
+#pragma unroll 1
+        for (int tt = 0; tt < 2 && live; ++tt) live = step(tt);
+        if (more) store_k_tile(stk, k_lds + (buf ^ 1) * kKTile);
+        StagingV stv;
+        load_v_tile(a, vbase, next_tok, stv);
+#pragma unroll 1
+        for (int tt = 2; tt < 4 && live; ++tt) live = step(tt);
+        if (more) store_v_tile(stv, v_lds + (buf ^ 1) * kVTile);
         __syncthreads();
     }
 
