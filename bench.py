@@ -209,8 +209,10 @@ def main() -> int:
         calls[i % copies](timer if i % EVENT_STRIDE == 0 else None)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    n_timed, (partial_ms, combine_ms) = timer.read()
+    partial_calls, combine_calls = timer.read_calls(args.steps)
+    n_timed = len(partial_calls)
     assert n_timed == (args.steps + EVENT_STRIDE - 1) // EVENT_STRIDE
+    partial_ms, combine_ms = sum(partial_calls), sum(combine_calls)
     ms_per_step = (t1 - t0) * 1e3 / args.steps
 
     # the same loop without the event records, for the record only
@@ -254,7 +256,8 @@ def main() -> int:
         # derived: attention-only bound on generated tokens/s if a 64-layer model made this call per layer
         "derived_tokens_per_s_64_layers": round(w.batch / (64 * ms_per_step * 1e-3), 1),
         "ms_per_step_without_event_records": round(ms_plain, 5),
-        "kernel_ms": {"partial": round(partial_avg_ms, 5),
+        "kernel_ms": {"partial": round(partial_avg_ms, 5), "partial_median": round(float(np.median(partial_calls)), 5),
+                      "partial_min": round(min(partial_calls), 5),
                       "combine": round(combine_ms / n_timed, 5), "launches_timed": n_timed},
         "roofline": {
             "kernel": "partial_mfma_kernel" if args.variant == 0 else "partial_valu_kernel",

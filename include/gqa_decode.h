@@ -153,8 +153,12 @@ int gqa_decode_attn(const gqa_decode_params* params,
  * gqa_timer_read waits for the last recorded event and returns, summed over
  * the calls recorded since the last reset, the elapsed milliseconds of
  * {split-KV partial, combine} in host_kernel_ms[2] and the number of calls in
- * *host_calls; it then resets the timer.  Creating, reading and
- * destroying a timer are not for hot loops; recording is.
+ * *host_calls; it then resets the timer.  gqa_timer_read_calls does the same but
+ * returns the elapsed milliseconds of every recorded call, in call order, in
+ * host_partial_ms[capacity] and host_combine_ms[capacity] (either may be NULL);
+ * more recorded calls than `capacity` is an invalid-argument error and leaves the
+ * timer untouched.  Creating, reading and destroying a timer are not for hot
+ * loops; recording is.
  * A timer serves one stream at a time and is not thread-safe.
  */
 typedef struct gqa_timer gqa_timer;
@@ -162,6 +166,8 @@ typedef struct gqa_timer gqa_timer;
 int  gqa_timer_create(int32_t max_calls, gqa_timer** host_out);
 void gqa_timer_destroy(gqa_timer* timer);
 int  gqa_timer_read(gqa_timer* timer, int32_t* host_calls, float host_kernel_ms[2]);
+int  gqa_timer_read_calls(gqa_timer* timer, int32_t capacity, int32_t* host_calls,
+                          float* host_partial_ms, float* host_combine_ms);
 
 int gqa_decode_attn_timed(const gqa_decode_params* params,
                           const void* q, const void* k, const void* v,

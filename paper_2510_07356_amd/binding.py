@@ -25,7 +25,7 @@ GQA_ERR_LAUNCH = -4
 
 EXPORTS = ("gqa_decode_version", "gqa_decode_strerror", "gqa_decode_workspace_bytes",
            "gqa_decode_plan_info", "gqa_decode_attn", "gqa_decode_attn_timed",
-           "gqa_prefill_attn", "gqa_decode_kv_append", "gqa_cascade_workspace_bytes", "gqa_decode_attn_shared_prefix", "gqa_decode_stream_read", "gqa_decode_stream_copy", "gqa_timer_create", "gqa_timer_destroy", "gqa_timer_read")
+           "gqa_prefill_attn", "gqa_decode_kv_append", "gqa_cascade_workspace_bytes", "gqa_decode_attn_shared_prefix", "gqa_decode_stream_read", "gqa_decode_stream_copy", "gqa_timer_create", "gqa_timer_destroy", "gqa_timer_read", "gqa_timer_read_calls")
 
 
 class gqa_decode_params(ctypes.Structure):
@@ -106,6 +106,9 @@ def _load() -> ctypes.CDLL:
     lib.gqa_timer_destroy.argtypes = [vp]
     lib.gqa_timer_read.restype = ctypes.c_int
     lib.gqa_timer_read.argtypes = [vp, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_float)]
+    lib.gqa_timer_read_calls.restype = ctypes.c_int
+    lib.gqa_timer_read_calls.argtypes = [vp, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32),
+                                         ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float)]
     lib.gqa_cascade_workspace_bytes.restype = ctypes.c_size_t
     lib.gqa_cascade_workspace_bytes.argtypes = [ctypes.POINTER(gqa_cascade_params)]
     lib.gqa_decode_attn_shared_prefix.restype = ctypes.c_int
@@ -216,6 +219,15 @@ class Timer:
         if rc != GQA_OK:
             raise GqaError(rc)
         return n.value, tuple(ms)
+
+    def read_calls(self, capacity: int):
+        """Wait for the recorded calls; returns (partial_ms, combine_ms), one list entry per call."""
+        n = ctypes.c_int32(0)
+        a, b = (ctypes.c_float * capacity)(), (ctypes.c_float * capacity)()
+        rc = _lib.gqa_timer_read_calls(self._h, int(capacity), ctypes.byref(n), a, b)
+        if rc != GQA_OK:
+            raise GqaError(rc)
+        return list(a[:n.value]), list(b[:n.value])
 
     def close(self):
         if self._h:

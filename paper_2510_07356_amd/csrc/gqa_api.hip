@@ -278,6 +278,30 @@ int gqa_timer_read(gqa_timer* timer, int32_t* host_calls, float host_kernel_ms[2
     return status;
 }
 
+int gqa_timer_read_calls(gqa_timer* timer, int32_t capacity, int32_t* host_calls,
+                         float* host_partial_ms, float* host_combine_ms) {
+    if (timer == nullptr || capacity < 0 || timer->calls > capacity) return GQA_ERR_INVALID_ARG;
+    int status = GQA_OK;
+    if (timer->calls > 0 &&
+        hipEventSynchronize(timer->events[3 * (size_t)timer->calls - 1]) != hipSuccess)
+        status = GQA_ERR_LAUNCH;
+    for (int c = 0; c < timer->calls && status == GQA_OK; ++c) {
+        float* dst[2] = {host_partial_ms, host_combine_ms};
+        for (int i = 0; i < 2; ++i) {
+            float ms = 0.f;
+            if (hipEventElapsedTime(&ms, timer->events[3 * (size_t)c + i],
+                                    timer->events[3 * (size_t)c + i + 1]) != hipSuccess) {
+                status = GQA_ERR_LAUNCH;
+                break;
+            }
+            if (dst[i] != nullptr) dst[i][c] = ms;
+        }
+    }
+    if (host_calls) *host_calls = timer->calls;
+    timer->calls = 0;
+    return status;
+}
+
 namespace {
 
 struct CascadePlan {

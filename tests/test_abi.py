@@ -43,6 +43,14 @@ def test_curation_header_and_library_agree(lib):
         assert hasattr(raw, n), n
 
 
+def test_timer_rejects_bad_arguments():
+    raw = ctypes.CDLL(LIB)
+    raw.gqa_timer_read_calls.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    assert raw.gqa_timer_read_calls(None, 4, None, None, None) == -1
+    raw.gqa_timer_read.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    assert raw.gqa_timer_read(None, None, None) == -1
+
+
 def test_version_and_strerror(lib):
     assert lib.gqa_decode_version() >= 100
     assert lib.gqa_decode_strerror(0) == "ok"

@@ -219,6 +219,28 @@ def test_timer_reports_both_kernels(binding):
     check(w, out, lse, oracle_of(w), "timer")
 
 
+def test_timer_per_call_readout(binding):
+    """Three recorded calls come back as three positive (partial, combine) pairs; a capacity below
+    the number of recorded calls is refused and leaves the timer readable."""
+    import torch
+    w = wl.make_contiguous("timer_calls", 114, 4, 40, 8, [2048] * 4)
+    dev = binding.to_device(w)
+    params = binding.make_params(dev["q"], dev["k"], dev["v"], w.max_kv_len, w.scale, 0, None, 0, 0)
+    ws = torch.empty(binding.gqa_decode_workspace_bytes(params), dtype=torch.uint8, device="cuda:0")
+    out = torch.empty((w.batch, w.num_q_heads, w.head_dim), dtype=torch.float32, device="cuda:0")
+    call = binding.Call(params, dev["q"], dev["k"], dev["v"], dev["kv_lens"], None, None, out, None, ws)
+    timer = binding.Timer(8)
+    for _ in range(3):
+        call(timer)
+    with pytest.raises(binding.GqaError):
+        timer.read_calls(2)
+    partial, combine = timer.read_calls(8)
+    assert len(partial) == 3 and len(combine) == 3
+    assert all(0.0 < x < 50.0 for x in partial + combine)
+    assert timer.read() == (0, (0.0, 0.0))
+    timer.close()
+
+
 # --------------------------------------------------------------------------- the five configurations, full size
 
 @pytest.mark.parametrize("index", [0, 1, 2, 3, 4])
