@@ -144,6 +144,93 @@ def bench_prefill(args) -> int:
     return 0
 
 
+def bench_decode_step(args) -> int:
+    """One decode step of an L-layer model on the ragged 64-sequence batch with a paged cache: per
+    layer the new token's K/V are appended (rotary included) and attention runs over that layer's
+    cache.  All layers' caches stay resident (L x 2.4 GB), the step is captured once in a HIP graph
+    and replayed; layer 0 is checked against the oracle."""
+    import numpy as np
+    import torch
+    from paper_2510_07356_amd import binding, workloads
+    torch.cuda.set_device(0)
+    L = args.layers
+    lens = workloads.ragged_lengths(2, 64, 1024, 16384)          # the lengths of the headline batch
+    w = workloads.make_paged("ragged_b64_1k_16k_paged", 2, 64, 40, 8, lens, table_width=16384 // workloads.PAGE)
+    base = binding.to_device(w)
+    free, _ = torch.cuda.mem_get_info()
+    need = (L - 1) * 2 * base["k"].numel() * 2
+    if need > free - (8 << 30):
+        print(f"bench.py: {L} layers need {need / 2**30:.0f} GiB of cache, {free / 2**30:.0f} GiB free", file=sys.stderr)
+        return 2
+    # the other layers hold the same values in memory of their own (the values do not matter for the timing)
+    layers = [base] + [dict(base, k=base["k"].clone(), v=base["v"].clone()) for _ in range(L - 1)]
+    positions = int(w.max_kv_len)
+    d = np.arange(64, dtype=np.float64)
+    ang = np.arange(positions, dtype=np.float64)[:, None] * 1.0e6 ** (-2.0 * d / 128)[None, :]
+    table = np.concatenate([np.cos(ang), np.sin(ang)], axis=1).astype(np.float32)
+    cs = torch.from_numpy(table).to("cuda:0")
+    g = torch.Generator(device="cuda:0").manual_seed(12)
+    q_in = base["q"]
+    k_new = torch.randn((64, 8, 128), generator=g, device="cuda:0").to(torch.bfloat16)
+    v_new = torch.randn((64, 8, 128), generator=g, device="cuda:0").to(torch.bfloat16)
+    q_rot = torch.empty_like(q_in)
+    params = binding.make_params(q_rot, base["k"], base["v"], positions, w.scale, w.page_size, base["block_table"], 0, 0)
+    ws = torch.empty(binding.gqa_decode_workspace_bytes(params), dtype=torch.uint8, device="cuda:0")
+    out = torch.empty((64, 40, 128), dtype=torch.float32, device="cuda:0")
+
+    def step():
+        for lay in layers:
+            binding.gqa_decode_kv_append(q_in, q_rot, k_new, v_new, lay["k"], lay["v"], base["kv_lens"], positions,
+                                         base["block_table"], w.page_size, cs)
+            binding.gqa_decode_attn(params, q_rot, lay["k"], lay["v"], base["kv_lens"], base["block_table"], None,
+                                    out, None, ws)
+
+    step()                                                        # eager once: device properties are cached
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    eager_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for _ in range(args.warmup):
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    kv_bytes = L * w.kv_bytes
+    result = {
+        "metric": "decode_step_kv_read_throughput", "value": round(kv_bytes / (ms * 1e-3) / 1e12, 4), "unit": "TB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{L} layers x (KV append with rotary + attention) on {w.name}: B=64 Hq=40 Hkv=8 D=128 "
+                               f"kv_tokens={w.kv_tokens} per layer, paged, one HIP graph per step",
+                   "layers": L, "resident_cache_bytes": L * 2 * base["k"].numel() * 2, "kv_bytes_per_step": kv_bytes},
+        "pct_of_hbm_peak": round(100.0 * kv_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2),
+        "ms_per_step_eager_launches": round(eager_ms, 4),
+        "tokens_per_s_attention_only": round(64 / (ms * 1e-3), 1),
+    }
+    if not args.no_cpu_baseline:
+        from oracle import decode_attn, kv_append
+        kn = k_new.view(torch.int16).cpu().numpy().view(np.uint16)
+        vn = v_new.view(torch.int16).cpu().numpy().view(np.uint16)
+        q_ref = kv_append(w.q, kn, vn, w.k, w.v, w.kv_lens, cos_sin=table, block_table=w.block_table, page_size=w.page_size)
+        ref = decode_attn(q_ref, w.k, w.v, w.kv_lens, w.scale, block_table=w.block_table, page_size=w.page_size)
+        binding.gqa_decode_kv_append(q_in, q_rot, k_new, v_new, base["k"], base["v"], base["kv_lens"], positions,
+                                     base["block_table"], w.page_size, cs)
+        binding.gqa_decode_attn(params, q_rot, base["k"], base["v"], base["kv_lens"], base["block_table"], None, out, None, ws)
+        torch.cuda.synchronize()
+        err = out.double().cpu().numpy() - ref.out
+        result["parity"] = {"max_abs": float(np.abs(err).max()), "rel_l2": float(np.linalg.norm(err) / np.linalg.norm(ref.out))}
+    print(json.dumps(result), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -162,6 +249,9 @@ def main() -> int:
                     help="benchmark the shared-prefix entry point on a tasks x samples batch instead")
     ap.add_argument("--prefill", action="store_true", help="benchmark causal prefill attention instead")
     ap.add_argument("--seq-len", type=int, default=32768)
+    ap.add_argument("--decode-step", action="store_true",
+                    help="benchmark one graph-captured decode step of --layers layers (append + attention per layer)")
+    ap.add_argument("--layers", type=int, default=64)
     ap.add_argument("--tasks", type=int, default=12)
     ap.add_argument("--samples", type=int, default=5)
     ap.add_argument("--copies", type=int, default=0, help="cache copies to rotate over (0 = enough for 1 GiB)")
@@ -182,6 +272,8 @@ def main() -> int:
         return bench_shared_prefix(args)
     if args.prefill:
         return bench_prefill(args)
+    if args.decode_step:
+        return bench_decode_step(args)
     torch.cuda.set_device(0)
     t_gen = time.time()
     w = workloads.make_config(args.config, layout=args.layout)
