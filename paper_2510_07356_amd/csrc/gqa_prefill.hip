@@ -339,12 +339,11 @@ constexpr size_t kPrefillLds = (size_t)(2 * kKTile + 2 * kVTile) * sizeof(uint16
 }  // namespace
 
 hipError_t launch_prefill(const PrefillArgs& a, hipStream_t s) {
-    static bool configured = false;
-    if (!configured) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_kernel),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPrefillLds);
-        configured = true;
-    }
+    // more than the default 64 KB of LDS: the limit is a per-device attribute of the kernel, set on every
+    // launch (a few microseconds against milliseconds of kernel) so that each device a process uses has it
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)kPrefillLds) != hipSuccess)
+        return hipErrorInvalidValue;
     const int n_qb = (a.seq_len + kBM - 1) / kBM;
     const int heads_per_xcd = (a.num_kv_heads + 7) / 8;
     const int64_t grid = 8LL * a.group * n_qb * heads_per_xcd * a.batch;
