@@ -253,6 +253,16 @@ int gqa_prefill_attn(const gqa_prefill_params* params, const void* q, const void
                      float* out, float* lse, void* stream);
 
 /*
+ * The same over a batch of prompts of different lengths (the prompts of the paper's tasks differ in
+ * length; Section 3.3 samples each of them several times).  seq_lens[b] (device, int32, clamped to
+ * [0, seq_len]) is the number of tokens of sequence b; tensors keep the padded [B, T = seq_len, ...]
+ * layout.  Rows t >= seq_lens[b] of out / lse are not written and their q / k / v are not read.
+ * seq_lens == NULL means every sequence has seq_len tokens (= gqa_prefill_attn).
+ */
+int gqa_prefill_attn_varlen(const gqa_prefill_params* params, const void* q, const void* k, const void* v,
+                            const int32_t* seq_lens, float* out, float* lse, void* stream);
+
+/*
  * The step before attention in a decode layer: append the new token's key and
  * value rows to the cache and, optionally, apply the rotary position embedding
  * to the new key and to the query (the 32B model family whose traces the paper

@@ -25,7 +25,7 @@ GQA_ERR_LAUNCH = -4
 
 EXPORTS = ("gqa_decode_version", "gqa_decode_strerror", "gqa_decode_workspace_bytes",
            "gqa_decode_plan_info", "gqa_decode_attn", "gqa_decode_attn_timed",
-           "gqa_prefill_attn", "gqa_decode_kv_append", "gqa_cascade_workspace_bytes", "gqa_decode_attn_shared_prefix", "gqa_decode_stream_read", "gqa_decode_stream_copy", "gqa_timer_create", "gqa_timer_destroy", "gqa_timer_read", "gqa_timer_read_calls")
+           "gqa_prefill_attn", "gqa_prefill_attn_varlen", "gqa_decode_kv_append", "gqa_cascade_workspace_bytes", "gqa_decode_attn_shared_prefix", "gqa_decode_stream_read", "gqa_decode_stream_copy", "gqa_timer_create", "gqa_timer_destroy", "gqa_timer_read", "gqa_timer_read_calls")
 
 
 class gqa_decode_params(ctypes.Structure):
@@ -115,6 +115,8 @@ def _load() -> ctypes.CDLL:
     lib.gqa_decode_attn_shared_prefix.argtypes = [ctypes.POINTER(gqa_cascade_params)] + [vp] * 13 + [ctypes.c_size_t, vp]
     lib.gqa_prefill_attn.restype = ctypes.c_int
     lib.gqa_prefill_attn.argtypes = [ctypes.POINTER(gqa_prefill_params)] + [vp] * 6
+    lib.gqa_prefill_attn_varlen.restype = ctypes.c_int
+    lib.gqa_prefill_attn_varlen.argtypes = [ctypes.POINTER(gqa_prefill_params)] + [vp] * 7
     lib.gqa_decode_kv_append.restype = ctypes.c_int
     lib.gqa_decode_kv_append.argtypes = [ctypes.POINTER(gqa_append_params)] + [vp] * 10
     lib.gqa_decode_stream_read.restype = ctypes.c_int
@@ -357,9 +359,13 @@ def run_shared_prefix(sw, dev=None, chunk_tokens: int = 0, want_lse: bool = True
 
 
 def gqa_prefill_attn(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, scale: float, out: torch.Tensor,
-                     lse: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None) -> None:
+                     lse: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None,
+                     seq_lens: Optional[torch.Tensor] = None) -> None:
     """q [B, T, Hq, D], k/v [B, T, Hkv, D] bf16 (any strides, dense last axis); out [B, T, Hq, D] fp32;
-    lse [B, T, Hq] fp32 dense or None."""
+    lse [B, T, Hq] fp32 dense or None; seq_lens [B] int32 on the device or None (gqa_prefill_attn_varlen)."""
+    if seq_lens is not None and (not seq_lens.is_cuda or seq_lens.dtype != torch.int32 or not seq_lens.is_contiguous()
+                                 or seq_lens.numel() != q.shape[0]):
+        raise TypeError("seq_lens must be a dense int32 device tensor with one entry per sequence")
     for t in (q, k, v):
         if not t.is_cuda or t.dtype != torch.bfloat16 or t.stride(-1) != 1:
             raise TypeError("bf16 device tensors with a dense last axis expected")
@@ -376,8 +382,13 @@ def gqa_prefill_attn(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, scale: f
     p.v_stride_b, p.v_stride_t, p.v_stride_h = v.stride(0), v.stride(1), v.stride(2)
     p.o_stride_b, p.o_stride_t, p.o_stride_h = out.stride(0), out.stride(1), out.stride(2)
     s = stream if stream is not None else torch.cuda.current_stream(q.device)
-    rc = _lib.gqa_prefill_attn(ctypes.byref(p), q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(),
-                               lse.data_ptr() if lse is not None else None, s.cuda_stream)
+    if seq_lens is None:
+        rc = _lib.gqa_prefill_attn(ctypes.byref(p), q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(),
+                                   lse.data_ptr() if lse is not None else None, s.cuda_stream)
+    else:
+        rc = _lib.gqa_prefill_attn_varlen(ctypes.byref(p), q.data_ptr(), k.data_ptr(), v.data_ptr(),
+                                          seq_lens.data_ptr(), out.data_ptr(),
+                                          lse.data_ptr() if lse is not None else None, s.cuda_stream)
     if rc != GQA_OK:
         raise GqaError(rc)
 

@@ -431,6 +431,11 @@ int gqa_decode_attn_shared_prefix(const gqa_cascade_params* cp, const void* q, c
 
 int gqa_prefill_attn(const gqa_prefill_params* p, const void* q, const void* k, const void* v, float* out,
                      float* lse, void* stream) {
+    return gqa_prefill_attn_varlen(p, q, k, v, nullptr, out, lse, stream);
+}
+
+int gqa_prefill_attn_varlen(const gqa_prefill_params* p, const void* q, const void* k, const void* v,
+                            const int32_t* seq_lens, float* out, float* lse, void* stream) {
     if (p == nullptr) return GQA_ERR_INVALID_ARG;
     if (p->batch < 1 || p->seq_len < 1 || p->num_q_heads < 1 || p->num_kv_heads < 1) return GQA_ERR_INVALID_ARG;
     if (p->num_q_heads % p->num_kv_heads != 0 || !std::isfinite(p->scale)) return GQA_ERR_INVALID_ARG;
@@ -451,6 +456,7 @@ int gqa_prefill_attn(const gqa_prefill_params* p, const void* q, const void* k, 
     a.v = static_cast<const uint16_t*>(v);
     a.out = out;
     a.lse = lse;
+    a.seq_lens = seq_lens;
     a.batch = p->batch; a.seq_len = p->seq_len;
     a.num_q_heads = p->num_q_heads; a.num_kv_heads = p->num_kv_heads; a.group = group;
     a.q_stride_b = p->q_stride_b; a.q_stride_t = p->q_stride_t; a.q_stride_h = p->q_stride_h;

@@ -212,7 +212,8 @@ struct PrefillArgs {
     const uint16_t* v;
     float* out;              // [batch, seq, Hq, D] via strides
     float* lse;              // [batch, seq, Hq] dense, may be null
-    int32_t batch, seq_len, num_q_heads, num_kv_heads, group;
+    const int32_t* seq_lens; // [batch] tokens per sequence (clamped to [0, seq_len]), null: all have seq_len
+    int32_t batch, seq_len, num_q_heads, num_kv_heads, group;   // seq_len: the padded length T of the tensors
     int64_t q_stride_b, q_stride_t, q_stride_h;
     int64_t k_stride_b, k_stride_t, k_stride_h;
     int64_t v_stride_b, v_stride_t, v_stride_h;

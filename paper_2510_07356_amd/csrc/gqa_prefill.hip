@@ -75,10 +75,10 @@ __device__ __forceinline__ float max_across_halves(float x) {
 struct StagingK { uint4 r0, r1, r2, r3; };   // token (tid / 16) + 32 i, 16-byte piece tid % 16
 struct StagingV { uint4 r0, r1, r2, r3; };   // tokens 4 * (tid / 16) + i, 16-byte piece tid % 16
 
-__device__ __forceinline__ void load_k_tile(const PrefillArgs& a, const uint16_t* kbase, int tok0, StagingK& st) {
+__device__ __forceinline__ void load_k_tile(const PrefillArgs& a, const uint16_t* kbase, int tok0, int len, StagingK& st) {
     const int tid = threadIdx.x;
     const int piece = tid & 15, grp = tid >> 4;
-    if (tok0 + kBN <= a.seq_len) {
+    if (tok0 + kBN <= len) {
         // whole tile inside the sequence: one per-thread pointer, wave-uniform row offsets
         const uint16_t* kp = kbase + (int64_t)tok0 * a.k_stride_t + ((int64_t)grp * a.k_stride_t + 8 * piece);
         const int64_t k32 = 32 * a.k_stride_t;
@@ -87,7 +87,7 @@ __device__ __forceinline__ void load_k_tile(const PrefillArgs& a, const uint16_t
         st.r2 = *reinterpret_cast<const uint4*>(kp + 2 * k32);
         st.r3 = *reinterpret_cast<const uint4*>(kp + 3 * k32);
     } else {
-        const int last = a.seq_len - 1;                 // rows beyond the sequence re-read the last row
+        const int last = max(len - 1, 0);               // rows beyond the sequence re-read the last row
         auto row = [&](int i) {
             return *reinterpret_cast<const uint4*>(kbase + (int64_t)min(tok0 + grp + 32 * i, last) * a.k_stride_t + 8 * piece);
         };
@@ -95,17 +95,17 @@ __device__ __forceinline__ void load_k_tile(const PrefillArgs& a, const uint16_t
     }
 }
 
-__device__ __forceinline__ void load_v_tile(const PrefillArgs& a, const uint16_t* vbase, int tok0, StagingV& st) {
+__device__ __forceinline__ void load_v_tile(const PrefillArgs& a, const uint16_t* vbase, int tok0, int len, StagingV& st) {
     const int tid = threadIdx.x;
     const int piece = tid & 15, grp = tid >> 4;
-    if (tok0 + kBN <= a.seq_len) {
+    if (tok0 + kBN <= len) {
         const uint16_t* vp = vbase + (int64_t)tok0 * a.v_stride_t + ((int64_t)(4 * grp) * a.v_stride_t + 8 * piece);
         st.r0 = *reinterpret_cast<const uint4*>(vp);
         st.r1 = *reinterpret_cast<const uint4*>(vp + a.v_stride_t);
         st.r2 = *reinterpret_cast<const uint4*>(vp + 2 * a.v_stride_t);
         st.r3 = *reinterpret_cast<const uint4*>(vp + 3 * a.v_stride_t);
     } else {
-        const int last = a.seq_len - 1;
+        const int last = max(len - 1, 0);
         auto row = [&](int i) {
             return *reinterpret_cast<const uint4*>(vbase + (int64_t)min(tok0 + 4 * grp + i, last) * a.v_stride_t + 8 * piece);
         };
@@ -160,12 +160,14 @@ __global__ __launch_bounds__(kPrefillThreads, 1) __attribute__((amdgpu_waves_per
     const int g = xcd + 8 * (s % heads_per_xcd); s /= heads_per_xcd;
     const int b = s;
     if (g >= a.num_kv_heads) return;
+    // tokens of this sequence; a.seq_len is the padded length the tensors and the grid are laid out for
+    const int len = a.seq_lens != nullptr ? min(max(uniform_i32(a.seq_lens, b), 0), a.seq_len) : a.seq_len;
     const int h = g * G + hh;
 
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n = lane & 31, kb = lane >> 5;
     const int q0 = qb * kBM + wave * kWaveRows;              // first query row of this wavefront
-    const int q_last = min(q0 + kWaveRows, a.seq_len) - 1;   // may be < q0: wavefront without rows
+    const int q_last = min(q0 + kWaveRows, len) - 1;   // may be < q0: wavefront without rows
     const float c = fabsf(a.scale_log2e);                    // a negative scale is applied by negating Q (exact)
     const uint32_t qsign = a.scale_log2e < 0.f ? 0x80008000u : 0u;
 
@@ -176,7 +178,7 @@ __global__ __launch_bounds__(kPrefillThreads, 1) __attribute__((amdgpu_waves_per
     // Q^T as B operands: column n of block nt is query row q0 + 32 nt + n, step st covers columns 16 st + 8 kb + e
     uint4 qf[8];
     {
-        const int qr = min(q0 + n, a.seq_len - 1);
+        const int qr = min(q0 + n, max(len - 1, 0));
         const uint16_t* qrow = qbase + (int64_t)qr * a.q_stride_t;
 #pragma unroll
         for (int st = 0; st < 8; ++st) {
@@ -194,14 +196,16 @@ __global__ __launch_bounds__(kPrefillThreads, 1) __attribute__((amdgpu_waves_per
     float m = -INFINITY, l = 0.f;          // running maximum of the raw scores (times |scale| log2 e in the exponent)
     const int qrow = q0 + n;
 
-    const int kv_end = min(qb * kBM + kBM, a.seq_len);        // keys this workgroup needs: [0, kv_end)
-    const int n_tiles = (kv_end + kBN - 1) / kBN;
+    const int kv_end = min(qb * kBM + kBM, len);        // keys this workgroup needs: [0, kv_end)
+    // a block beyond the end of its sequence stages one tile, walks none and writes nothing (leaving the
+    // kernel early instead costs the other blocks 2 % in the code the compiler then lays out)
+    const int n_tiles = qb * kBM < len ? (kv_end + kBN - 1) / kBN : 0;
 
     {
         StagingK k0;
         StagingV v0;
-        load_k_tile(a, kbase, 0, k0);
-        load_v_tile(a, vbase, 0, v0);
+        load_k_tile(a, kbase, 0, len, k0);
+        load_v_tile(a, vbase, 0, len, v0);
         store_k_tile(k0, k_lds);
         store_v_tile(v0, v_lds);
     }
@@ -212,7 +216,7 @@ __global__ __launch_bounds__(kPrefillThreads, 1) __attribute__((amdgpu_waves_per
         const bool more = tile + 1 < n_tiles;
         const int next_tok = (more ? tile + 1 : tile) * kBN;   // the last iteration re-reads its own tile (never stored)
         StagingK stk;
-        load_k_tile(a, kbase, next_tok, stk);
+        load_k_tile(a, kbase, next_tok, len, stk);
 
         const uint16_t* ks = k_lds + buf * kKTile;
         const uint16_t* vs = v_lds + buf * kVTile;
@@ -304,7 +308,7 @@ __global__ __launch_bounds__(kPrefillThreads, 1) __attribute__((amdgpu_waves_per
         for (int tt = 0; tt < 2 && live; ++tt) live = step(tt);
         if (more) store_k_tile(stk, k_lds + (buf ^ 1) * kKTile);
         StagingV stv;
-        load_v_tile(a, vbase, next_tok, stv);
+        load_v_tile(a, vbase, next_tok, len, stv);
 #pragma unroll 1
         for (int tt = 2; tt < 4 && live; ++tt) live = step(tt);
         if (more) store_v_tile(stv, v_lds + (buf ^ 1) * kVTile);
@@ -315,7 +319,7 @@ __global__ __launch_bounds__(kPrefillThreads, 1) __attribute__((amdgpu_waves_per
     {
         float lt = l;
         lt += __shfl_xor(lt, 32);
-        if (qrow < a.seq_len) {
+        if (qrow < len) {
             const float inv = lt > 0.f ? 1.f / lt : 0.f;
             float* orow = a.out + (int64_t)b * a.o_stride_b + (int64_t)qrow * a.o_stride_t + (int64_t)h * a.o_stride_h;
 #pragma unroll

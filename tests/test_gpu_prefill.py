@@ -106,3 +106,28 @@ def test_long_sequence_sampled_rows(binding):
     rows = np.unique(np.concatenate([[0, 1, 31, 32, 63, 64, 255, 256, 257, 16383, 16384, T - 257, T - 256, T - 1],
                                      rng.integers(0, T, size=50)]))
     check_rows(out, lse, oracle_rows(q, k, v, 0, rows, scale), 0, rows, "prefill_32k")
+
+
+def test_ragged_prompt_batch(binding):
+    """Prompts of different lengths in one padded batch: every row below a sequence's length matches the
+    oracle, rows beyond it (and a whole empty sequence) are left untouched."""
+    import torch
+    B, T, Hq, Hkv = 5, 700, 40, 8
+    lens = [700, 1, 300, 0, 257]
+    q, k, v = make_inputs(31, B, T, Hq, Hkv)
+    scale = float(np.float32(1.0 / np.sqrt(128)))
+    dq, dk, dv = (binding._bf16_view(x).to("cuda:0") for x in (q, k, v))
+    # poison what lies beyond each sequence: it must not be read
+    for b, L in enumerate(lens):
+        dk[b, L:] = float("nan")
+        dv[b, L:] = float("nan")
+        dq[b, L:] = float("nan")
+    out = torch.full((B, T, Hq, 128), float("nan"), dtype=torch.float32, device="cuda:0")
+    lse = torch.full((B, T, Hq), float("nan"), dtype=torch.float32, device="cuda:0")
+    binding.gqa_prefill_attn(dq, dk, dv, scale, out, lse, seq_lens=torch.tensor(lens, dtype=torch.int32, device="cuda:0"))
+    torch.cuda.synchronize()
+    for b, L in enumerate(lens):
+        if L > 0:
+            rows = np.arange(L)
+            check_rows(out, lse, oracle_rows(q, k, v, b, rows, scale), b, rows, f"ragged b={b} len={L}")
+        assert torch.isnan(out[b, L:]).all() and torch.isnan(lse[b, L:]).all(), f"b={b}: rows beyond the length were written"
