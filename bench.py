@@ -110,34 +110,47 @@ def bench_shared_prefix(args) -> int:
 
 
 def bench_prefill(args) -> int:
-    """Causal prefill attention over one sequence of --seq-len tokens with the 32B head shape."""
+    """Causal prefill attention with the 32B head shape: one sequence of --seq-len tokens, or with
+    --prompts N a padded batch of N prompts whose lengths follow the prompt recipe of the sampling
+    batch (lognormal around 1,800 tokens, sigma 0.3)."""
     import numpy as np
     import torch
     from paper_2510_07356_amd import binding
     torch.cuda.set_device(0)
-    T, Hq, Hkv, D = args.seq_len, 40, 8, 128
+    Hq, Hkv, D = 40, 8, 128
+    if args.prompts > 0:
+        rng = np.random.default_rng([6, 0])
+        lens = np.clip(np.rint(np.exp(np.log(1800.0) + 0.3 * rng.standard_normal(args.prompts))), 16, 8192).astype(np.int32)
+        B, T = args.prompts, int(-(-int(lens.max()) // 256) * 256)
+        seq_lens = torch.from_numpy(lens).to("cuda:0")
+        what = f"causal prefill, {B} prompts of {int(lens.min())}-{int(lens.max())} tokens (sum {int(lens.sum())}) padded to {T}"
+    else:
+        B, T = 1, args.seq_len
+        lens, seq_lens = np.array([T], dtype=np.int64), None
+        what = f"causal prefill, one sequence of {T} tokens"
     g = torch.Generator(device="cuda:0").manual_seed(11)
-    q = torch.randn((1, T, Hq, D), generator=g, device="cuda:0", dtype=torch.float32).to(torch.bfloat16)
-    k = torch.randn((1, T, Hkv, D), generator=g, device="cuda:0", dtype=torch.float32).to(torch.bfloat16)
-    v = torch.randn((1, T, Hkv, D), generator=g, device="cuda:0", dtype=torch.float32).to(torch.bfloat16)
-    out = torch.empty((1, T, Hq, D), dtype=torch.float32, device="cuda:0")
+    q = torch.randn((B, T, Hq, D), generator=g, device="cuda:0", dtype=torch.float32).to(torch.bfloat16)
+    k = torch.randn((B, T, Hkv, D), generator=g, device="cuda:0", dtype=torch.float32).to(torch.bfloat16)
+    v = torch.randn((B, T, Hkv, D), generator=g, device="cuda:0", dtype=torch.float32).to(torch.bfloat16)
+    out = torch.empty((B, T, Hq, D), dtype=torch.float32, device="cuda:0")
     scale = float(np.float32(1.0 / np.sqrt(D)))
     for _ in range(args.warmup):
-        binding.gqa_prefill_attn(q, k, v, scale, out)
+        binding.gqa_prefill_attn(q, k, v, scale, out, seq_lens=seq_lens)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        binding.gqa_prefill_attn(q, k, v, scale, out)
+        binding.gqa_prefill_attn(q, k, v, scale, out, seq_lens=seq_lens)
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / args.steps
-    flops = 4.0 * D * Hq * T * (T + 1) / 2.0            # two matrix products over the causal half
+    L = lens.astype(np.float64)
+    flops = float((4.0 * D * Hq * L * (L + 1) / 2.0).sum())   # two matrix products over the causal half
     tflops = flops / (ms * 1e-3) / 1e12
     print(json.dumps({
         "metric": "causal_prefill_attention_throughput", "value": round(tflops, 2), "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"causal prefill, one sequence of {T} tokens, Hq={Hq} Hkv={Hkv} D={D}", "flops": flops},
-        "tokens_per_s": round(T / (ms * 1e-3), 1),
+        "config": {"workload": f"{what}, Hq={Hq} Hkv={Hkv} D={D}", "flops": flops},
+        "tokens_per_s": round(float(L.sum()) / (ms * 1e-3), 1),
         "roofline": {"kernel": "prefill_kernel", "bound": "mfma", "achieved": round(tflops, 2), "peak": 2500.0,
                      "unit": "TFLOP/s", "frac": round(tflops / 2500.0, 4), "traffic": None},
     }), flush=True)
@@ -249,6 +262,7 @@ def main() -> int:
                     help="benchmark the shared-prefix entry point on a tasks x samples batch instead")
     ap.add_argument("--prefill", action="store_true", help="benchmark causal prefill attention instead")
     ap.add_argument("--seq-len", type=int, default=32768)
+    ap.add_argument("--prompts", type=int, default=0, help="with --prefill: a ragged batch of this many prompts instead")
     ap.add_argument("--decode-step", action="store_true",
                     help="benchmark one graph-captured decode step of --layers layers (append + attention per layer)")
     ap.add_argument("--layers", type=int, default=64)
