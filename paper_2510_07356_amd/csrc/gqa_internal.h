@@ -24,7 +24,7 @@ constexpr int kHeadDim = 128;        // the only supported head size
 constexpr int kMaxGroup = 16;        // query heads per KV head served by one K/V read
 constexpr int kTileTokens = 32;      // one MFMA tile; the unit of the stream split
 constexpr int kChunkGranule = 32;    // chunk_tokens must be a multiple of this
-constexpr int kMinShareTiles = 4;    // shares are never shorter than this (128 tokens)
+constexpr int kMinShareTiles = 2;    // shares are never shorter than this (64 tokens)
 constexpr int kThreads = 256;        // workgroup size of the partial kernels
 
 // Device-side view of one call.  Strides are in bf16 elements.
