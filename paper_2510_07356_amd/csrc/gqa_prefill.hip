@@ -268,7 +268,8 @@ __global__ __launch_bounds__(kPrefillThreads, 1) __attribute__((amdgpu_waves_per
             tmax = max_across_halves(tmax);
             const float mn = fmaxf(m, tmax);                  // finite: token 0 is visible to every row
             if (__builtin_amdgcn_ballot_w64(mn > m) != 0) {
-                const float alpha = __builtin_amdgcn_exp2f((m - mn) * c);   // first tile: 2^(-inf) = 0
+                // first tile: nothing accumulated yet (and -inf * 0 would not be a number for a zero scale)
+                const float alpha = m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((m - mn) * c);
                 l *= alpha;
 #pragma unroll
                 for (int dt = 0; dt < 4; ++dt) acc[dt] *= alpha;

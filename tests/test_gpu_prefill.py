@@ -77,6 +77,16 @@ def test_first_row_is_the_first_value_row(binding):
     np.testing.assert_array_equal(out[0, 0].cpu().numpy(), wl.bf16_bits_to_f32(v[0, 0]))
 
 
+@pytest.mark.parametrize("scale", [0.0, -0.05, 1.5])
+def test_zero_negative_and_large_scale(binding, scale):
+    """scale 0: every row is the running mean of the values (the mask must not rely on -inf * 0);
+    a negative scale prefers the smallest raw scores; a large one makes the softmax nearly one-hot."""
+    q, k, v = make_inputs(455, 1, 300, 10, 2)
+    out, lse = run(binding, q, k, v, scale)
+    rows = np.arange(300)
+    check_rows(out, lse, oracle_rows(q, k, v, 0, rows, scale), 0, rows, f"prefill_scale_{scale}")
+
+
 def test_strided_inputs_and_group_sizes(binding):
     """Token-major projections sliced out of a fused QKV buffer, group sizes 1, 4 and 16."""
     import torch
