@@ -70,6 +70,16 @@ def test_single_group_equals_plain_attention_when_prefix_is_empty(binding):
     assert float((out - plain).abs().max()) <= 2e-3
 
 
+@pytest.mark.parametrize("scale", [0.0, -0.05, 1.5])
+@pytest.mark.parametrize("paged", [False, True])
+def test_zero_negative_and_large_scale(binding, scale, paged):
+    """scale 0: the mean over prefix and suffix together; a negative scale; a nearly one-hot softmax
+    whose winner may sit in the prefix or in the suffix."""
+    sw = wl.make_shared_prefix("casc_scale", 304, [5, 2, 1], [300, 40, 0], [120, 1, 0, 77, 500, 64, 9, 200],
+                               paged=paged, scale=scale)
+    check(sw, *binding.run_shared_prefix(sw), f"casc_scale_{scale}_paged{int(paged)}")
+
+
 def test_too_large_group_is_rejected(binding):
     sw = wl.make_shared_prefix("casc_big", 303, [13], [64], [10] * 13)       # 13 * 5 = 65 query rows > 64
     with pytest.raises(binding.GqaError) as e:
