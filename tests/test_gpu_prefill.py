@@ -87,6 +87,21 @@ def test_zero_negative_and_large_scale(binding, scale):
     check_rows(out, lse, oracle_rows(q, k, v, 0, rows, scale), 0, rows, f"prefill_scale_{scale}")
 
 
+def test_outlier_keys_move_the_running_maximum(binding):
+    """A few key rows scaled by 8 (as in the long-sequence decode configuration): rows after an outlier
+    are dominated by it, the running maximum jumps late in the walk and the accumulators are rescaled."""
+    scale = float(np.float32(1.0 / np.sqrt(128)))
+    T = 600
+    q, k, v = make_inputs(456, 1, T, 10, 2)
+    kf = wl.bf16_bits_to_f32(k)
+    for t in (5, 130, 131, 383, 599):
+        kf[0, t] *= 8.0
+    k = wl.f32_to_bf16_bits(kf)
+    out, lse = run(binding, q, k, v, scale)
+    rows = np.arange(T)
+    check_rows(out, lse, oracle_rows(q, k, v, 0, rows, scale), 0, rows, "prefill_outliers")
+
+
 def test_strided_inputs_and_group_sizes(binding):
     """Token-major projections sliced out of a fused QKV buffer, group sizes 1, 4 and 16."""
     import torch
