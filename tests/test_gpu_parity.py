@@ -187,6 +187,45 @@ def test_device_lengths_are_clamped_to_the_bound(binding):
     check(w, out, None, oracle_of(w), "clamp")
 
 
+def test_offsets_beyond_two_to_the_31_elements(binding):
+    """Sequences whose cache rows start more than 2^31 elements into the K/V buffers (a batch stride of
+    1.2e9 elements): the addressing is 64-bit throughout."""
+    import torch
+    lens = [300, 77, 513]
+    w = wl.make_contiguous("far", 115, 3, 40, 8, lens, cache_len=520)
+    stride_b = 1_200_000_000                                   # elements; sequence 2 starts at 2.4e9
+    span = 2 * stride_b + 8 * 520 * 128
+    dev = binding.to_device(w)
+    big = {}
+    for name in ("k", "v"):
+        flat = torch.empty(span, dtype=torch.bfloat16, device="cuda:0")
+        view = torch.as_strided(flat, (3, 8, 520, 128), (stride_b, 520 * 128, 128, 1))
+        view.copy_(dev[name])
+        big[name] = view
+    dev["k"], dev["v"] = big["k"], big["v"]
+    out, lse = binding.run_workload(w, dev=dev)
+    check(w, out, lse, oracle_of(w), "far_offsets")
+
+
+def test_paged_pool_beyond_two_to_the_31_elements(binding):
+    """A block pool whose blocks lie 3e7 elements apart: the blocks of the later sequences start beyond
+    2^31 elements."""
+    import torch
+    lens = [300, 77, 513, 1000]
+    w = wl.make_paged("far_paged", 116, 4, 40, 8, lens, table_width=64)
+    dev = binding.to_device(w)
+    nblk = dev["k"].shape[0]
+    stride_b = 30_000_000
+    assert (nblk - 1) * stride_b > 2**31
+    for name in ("k", "v"):
+        flat = torch.empty((nblk - 1) * stride_b + 8 * 16 * 128, dtype=torch.bfloat16, device="cuda:0")
+        view = torch.as_strided(flat, tuple(dev[name].shape), (stride_b, 16 * 128, 128, 1))
+        view.copy_(dev[name])
+        dev[name] = view
+    out, lse = binding.run_workload(w, dev=dev)
+    check(w, out, lse, oracle_of(w), "far_paged")
+
+
 def test_workspace_reuse_and_side_stream(binding):
     """One poisoned workspace serves two different calls in a row; the second runs on a side stream."""
     import torch
