@@ -358,6 +358,11 @@ def main() -> int:
             "cache_copies_rotated": copies,
         },
         "pct_of_hbm_peak": round(100.0 * value * 1e3 / HBM_PEAK_GBPS, 2),
+        # everything a call moves: K/V once, Q, the output, and the partial results written by the partial
+        # kernel and read back by the combine kernel (at most one piece per wavefront plus one per row)
+        "bytes_incl_q_out_partials": int(kv_bytes + w.batch * w.num_q_heads * w.head_dim * (2 + 4) + w.batch * w.num_q_heads * 4
+                                         + 2 * (plan.workgroups * 4 + w.batch * w.num_kv_heads)
+                                         * (w.num_q_heads // w.num_kv_heads) * (w.head_dim + 2) * 4),
         "sequences_per_s": round(w.batch / (ms_per_step * 1e-3), 1),
         # derived: attention-only bound on generated tokens/s if a 64-layer model made this call per layer
         "derived_tokens_per_s_64_layers": round(w.batch / (64 * ms_per_step * 1e-3), 1),
