@@ -102,8 +102,9 @@ size_t gqa_decode_workspace_bytes(const gqa_decode_params* params);
  * end into one stream of 32-token tiles and cuts it into equal shares; each
  * share is processed by one persistent worker (a wavefront of the default
  * kernel, a workgroup of variant 1) and yields one partial result per row it
- * touches.  chunk_tokens == 0 gives one share per worker; chunk_tokens > 0
- * fixes the share length and the workers take shares in turn.
+ * touches.  chunk_tokens == 0 gives one share per worker (never shorter than 64
+ * tokens, so short batches use fewer workers); chunk_tokens > 0 fixes the share
+ * length and the workers take shares in turn.
  *   *share_tokens   tokens per share: chunk_tokens if given; else, when
  *                   host_kv_lens (HOST pointer, may be NULL) is given and a
  *                   device is present, the length the device will compute; else 0
