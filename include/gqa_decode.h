@@ -47,7 +47,8 @@ typedef enum gqa_status {
     GQA_ERR_INVALID_ARG = -1,          /* null pointer, non-positive size, bad stride or alignment */
     GQA_ERR_UNSUPPORTED = -2,          /* head_dim != 128, group size > 16, page size not a power of two >= 16 */
     GQA_ERR_WORKSPACE_TOO_SMALL = -3,  /* workspace_bytes < gqa_decode_workspace_bytes(params) */
-    GQA_ERR_LAUNCH = -4                /* the HIP runtime refused a launch or an event call */
+    GQA_ERR_LAUNCH = -4,               /* the HIP runtime refused a launch or an event call */
+    GQA_ERR_SCRATCH_LIMIT = -5         /* gqa_decode_attn_static: the call needs more than the built-in scratch buffer */
 } gqa_status;
 
 /*
@@ -86,6 +87,19 @@ int gqa_decode_version(void);
 
 /* Static, never-null description of a status code. */
 const char* gqa_decode_strerror(int status);
+
+/*
+ * Per-device set-up, for the device that is current in the calling thread: looks up
+ * the device's compute-unit count and the kernels' occupancy (the persistent launch
+ * size), raises the prefill kernel's LDS limit and resolves the built-in scratch
+ * buffer of gqa_decode_attn_static.  Optional: every entry point does the part it
+ * needs on its first call on a device.  Those first calls query the runtime and
+ * must not happen while a stream of the process is being captured into a HIP graph,
+ * so a caller that captures calls gqa_decode_init() once per device beforehand
+ * (idempotent, thread-safe, cheap after the first time).  Returns GQA_OK, or
+ * GQA_ERR_LAUNCH if no usable device is current.
+ */
+int gqa_decode_init(void);
 
 /*
  * Bytes of device workspace gqa_decode_attn needs for these parameters (a
@@ -144,6 +158,37 @@ int gqa_decode_attn(const gqa_decode_params* params,
                     float* out, float* lse,
                     void* workspace, size_t workspace_bytes,
                     void* stream);
+
+/*
+ * gqa_decode_attn for callers that cannot hand over a workspace because they cannot
+ * allocate one: code under HIP-graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, kernels and results as gqa_decode_attn (bit for
+ * bit), but the partial results go to a scratch buffer built into the library: a
+ * file-scope device array of GQA_DECODE_STATIC_SCRATCH_BYTES that every device the
+ * library runs on holds from the first use until the process ends.  The call
+ * allocates nothing, frees nothing and does not synchronise.
+ *
+ * Limit: the call needs  256 + 4 (B + 1) + (W + B Hkv) (Hq / Hkv) 520  bytes (each
+ * term rounded up to 256), W = the persistent wavefronts the device runs (1,024 on
+ * MI355X; max_kv_len / chunk_tokens shares per row instead when chunk_tokens > 0).
+ * Beyond GQA_DECODE_STATIC_SCRATCH_BYTES it returns GQA_ERR_SCRATCH_LIMIT and
+ * launches nothing; all five benchmark shapes fit (the largest, B = 128 with 32 / 8
+ * heads, needs 4.3 MB).
+ *
+ * All calls on one device share that device's buffer: it keeps the previous call's
+ * contents (nothing in it has to start at zero: every word a call reads it has
+ * written first), calls on the same stream are ordered and safe, and calls that
+ * overlap on one device (different streams, different threads) race.  The first
+ * call on a device resolves the buffer's address (see gqa_decode_init).
+ */
+#define GQA_DECODE_STATIC_SCRATCH_BYTES (32u << 20)
+
+size_t gqa_decode_static_scratch_bytes(void);     /* = GQA_DECODE_STATIC_SCRATCH_BYTES */
+
+int gqa_decode_attn_static(const gqa_decode_params* params,
+                           const void* q, const void* k, const void* v,
+                           const int32_t* kv_lens, const int32_t* block_table,
+                           float* out, float* lse, void* stream);
 
 /*
  * Per-kernel timing without synchronising inside the measured region.
@@ -276,8 +321,12 @@ int gqa_prefill_attn_varlen(const gqa_prefill_params* params, const void* q, con
  * with rot the identity if cos_sin is NULL and otherwise, for d < 64,
  *     x'[d] = x[d] cos[L-1][d] - x[d+64] sin[L-1][d],
  *     x'[d+64] = x[d+64] cos[L-1][d] + x[d] sin[L-1][d],
- * evaluated in fp64 and rounded once to bf16 (nearest even).  A sequence with
- * kv_lens[b] <= 0 gets its query copied unchanged and writes nothing.
+ * evaluated in fp64 (both products are exact there; their difference or sum is
+ * rounded to fp64) and then rounded to bf16, nearest even, over the whole bf16
+ * range: results below 2^-126 are rounded on the sub-normal grid of spacing 2^-133
+ * (never flushed or truncated), zeros keep their sign, results at or beyond
+ * 2^128 - 2^119 become infinity, and a NaN result is stored as 0x7FC0.  A sequence
+ * with kv_lens[b] <= 0 gets its query copied unchanged and writes nothing.
  *
  *   q_in, q_out  [B, Hq, 128] bf16, both with q_stride_b / q_stride_h; may alias
  *   k_new, v_new [B, Hkv, 128] bf16, dense

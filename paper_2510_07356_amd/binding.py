@@ -23,9 +23,15 @@ GQA_ERR_UNSUPPORTED = -2
 GQA_ERR_WORKSPACE_TOO_SMALL = -3
 GQA_ERR_LAUNCH = -4
 
-EXPORTS = ("gqa_decode_version", "gqa_decode_strerror", "gqa_decode_workspace_bytes",
+GQA_ERR_SCRATCH_LIMIT = -5
+
+EXPORTS = ("gqa_decode_version", "gqa_decode_strerror", "gqa_decode_init", "gqa_decode_workspace_bytes",
            "gqa_decode_plan_info", "gqa_decode_attn", "gqa_decode_attn_timed",
-           "gqa_prefill_attn", "gqa_prefill_attn_varlen", "gqa_decode_kv_append", "gqa_cascade_workspace_bytes", "gqa_decode_attn_shared_prefix", "gqa_decode_stream_read", "gqa_decode_stream_copy", "gqa_timer_create", "gqa_timer_destroy", "gqa_timer_read", "gqa_timer_read_calls")
+           "gqa_decode_static_scratch_bytes", "gqa_decode_attn_static",
+           "gqa_prefill_attn", "gqa_prefill_attn_varlen", "gqa_decode_kv_append",
+           "gqa_cascade_workspace_bytes", "gqa_decode_attn_shared_prefix",
+           "gqa_decode_stream_read", "gqa_decode_stream_copy",
+           "gqa_timer_create", "gqa_timer_destroy", "gqa_timer_read", "gqa_timer_read_calls")
 
 
 class gqa_decode_params(ctypes.Structure):
@@ -100,6 +106,12 @@ def _load() -> ctypes.CDLL:
     lib.gqa_decode_attn.argtypes = attn_args
     lib.gqa_decode_attn_timed.restype = ctypes.c_int
     lib.gqa_decode_attn_timed.argtypes = attn_args + [vp]
+    lib.gqa_decode_init.restype = ctypes.c_int
+    lib.gqa_decode_init.argtypes = []
+    lib.gqa_decode_static_scratch_bytes.restype = ctypes.c_size_t
+    lib.gqa_decode_static_scratch_bytes.argtypes = []
+    lib.gqa_decode_attn_static.restype = ctypes.c_int
+    lib.gqa_decode_attn_static.argtypes = [P, vp, vp, vp, i32p, i32p, vp, vp, vp]
     lib.gqa_timer_create.restype = ctypes.c_int
     lib.gqa_timer_create.argtypes = [ctypes.c_int32, ctypes.POINTER(ctypes.c_void_p)]
     lib.gqa_timer_destroy.restype = None
@@ -135,6 +147,17 @@ def gqa_decode_version() -> int:
 
 def gqa_decode_strerror(status: int) -> str:
     return _lib.gqa_decode_strerror(int(status)).decode()
+
+
+def gqa_decode_init() -> None:
+    """Per-device set-up for torch's current device (needed only before a HIP-graph capture)."""
+    rc = _lib.gqa_decode_init()
+    if rc != GQA_OK:
+        raise GqaError(rc)
+
+
+def gqa_decode_static_scratch_bytes() -> int:
+    return int(_lib.gqa_decode_static_scratch_bytes())
 
 
 def gqa_decode_workspace_bytes(params: gqa_decode_params) -> int:
@@ -288,6 +311,26 @@ def gqa_decode_attn(params: gqa_decode_params, q: torch.Tensor, k: torch.Tensor,
     if rc != GQA_OK:
         raise GqaError(rc)
     return None
+
+
+def gqa_decode_attn_static(params: gqa_decode_params, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
+                           kv_lens: torch.Tensor, block_table: Optional[torch.Tensor],
+                           out: torch.Tensor, lse: Optional[torch.Tensor],
+                           stream: Optional[torch.cuda.Stream] = None) -> None:
+    """gqa_decode_attn on the library's built-in scratch buffer: no workspace argument, no allocation."""
+    for name, t, dt in (("q", q, torch.bfloat16), ("k", k, torch.bfloat16), ("v", v, torch.bfloat16),
+                        ("kv_lens", kv_lens, torch.int32), ("out", out, torch.float32)):
+        if not t.is_cuda or t.dtype != dt:
+            raise TypeError(f"{name} must be a {dt} device tensor")
+    if not out.is_contiguous() or (lse is not None and not lse.is_contiguous()):
+        raise ValueError("out and lse must be dense")
+    s = stream if stream is not None else torch.cuda.current_stream(q.device)
+    rc = _lib.gqa_decode_attn_static(ctypes.byref(params), q.data_ptr(), k.data_ptr(), v.data_ptr(),
+                                     kv_lens.data_ptr(),
+                                     block_table.data_ptr() if block_table is not None else None,
+                                     out.data_ptr(), lse.data_ptr() if lse is not None else None, s.cuda_stream)
+    if rc != GQA_OK:
+        raise GqaError(rc)
 
 
 def gqa_cascade_workspace_bytes(params: gqa_cascade_params) -> int:

@@ -33,6 +33,12 @@ struct Plan {
     size_t total_bytes() const { return header_bytes + prefix_bytes + ml_bytes + o_bytes; }
 };
 
+// Scratch buffer of gqa_decode_attn_static: one copy per device, in the code object's
+// zero-initialised data.  In host code the name is only a handle for hipGetSymbolAddress; the
+// device address it yields (kept per device below) is what kernels and launches receive.
+constexpr size_t kStaticScratchBytes = GQA_DECODE_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 int check_shape(const gqa_decode_params* p) {
     if (p == nullptr) return GQA_ERR_INVALID_ARG;
     if (p->batch < 1 || p->num_q_heads < 1 || p->num_kv_heads < 1 || p->max_kv_len < 0)
@@ -53,14 +59,16 @@ int check_shape(const gqa_decode_params* p) {
     return GQA_OK;
 }
 
-int make_plan(const gqa_decode_params* p, Plan* plan) {
+// `workers` is the number of shares when none is fixed: kMaxWorkers for a workspace sized without
+// looking at a device, the real number of persistent workers when the launch size is known.
+int make_plan(const gqa_decode_params* p, Plan* plan, int64_t workers = kMaxWorkers) {
     const int rc = check_shape(p);
     if (rc != GQA_OK) return rc;
     const int group = p->num_q_heads / p->num_kv_heads;
     plan->fixed_share_tiles = p->chunk_tokens / gqa::kTileTokens;
     plan->max_tiles = (int64_t)p->num_kv_heads * p->batch * gqa::tiles_of(p->max_kv_len);
     if (plan->max_tiles > 0x3fffffffLL) return GQA_ERR_UNSUPPORTED;     // stream positions are int32
-    int64_t shares = kMaxWorkers;
+    int64_t shares = workers;
     if (plan->fixed_share_tiles > 0) {
         const int64_t fixed = (plan->max_tiles + plan->fixed_share_tiles - 1) / plan->fixed_share_tiles;
         if (fixed > shares) shares = fixed;
@@ -90,23 +98,52 @@ int workgroups_for(int variant) {
     return n;
 }
 
-int run(const gqa_decode_params* p, const void* q, const void* k, const void* v,
-        const int32_t* kv_lens, const int32_t* block_table, const int32_t* host_kv_lens,
-        float* out, float* lse, void* workspace, size_t workspace_bytes, void* stream,
-        gqa_timer* timer) {
-    (void)host_kv_lens;      // the launch size does not depend on the lengths
-    Plan plan;
-    const int rc = make_plan(p, &plan);
-    if (rc != GQA_OK) return rc;
-    if (!q || !k || !v || !kv_lens || !out || !workspace) return GQA_ERR_INVALID_ARG;
+// Persistent workgroups one call launches: the device's capacity, but no more than the stream can
+// feed with shares of the minimum length.
+int launch_workgroups(const gqa_decode_params* p, int64_t max_tiles) {
+    int workgroups = workgroups_for(p->kernel_variant);
+    if (workgroups < 1) return 0;
+    const int per_group = p->kernel_variant == 1 ? 1 : gqa::partial_mfma_workers_per_group();
+    const int64_t useful = (max_tiles + gqa::kMinShareTiles * per_group - 1) / (gqa::kMinShareTiles * per_group);
+    if (useful < workgroups) workgroups = (int)(useful > 0 ? useful : 1);
+    return workgroups;
+}
+
+// Device address of this device's copy of `scratch`, looked up once per device.
+int static_scratch(void** out) {
+    static std::atomic<void*> cache[kMaxDevices];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return GQA_ERR_LAUNCH;
+    void* ptr = cache[dev].load(std::memory_order_acquire);
+    if (ptr == nullptr) {
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return GQA_ERR_LAUNCH;
+        cache[dev].store(ptr, std::memory_order_release);
+    }
+    *out = ptr;
+    return GQA_OK;
+}
+
+// Host-side checks of the tensors of one call (the shape was checked by make_plan).
+int check_tensors(const gqa_decode_params* p, const void* q, const void* k, const void* v,
+                  const int32_t* kv_lens, const int32_t* block_table, const float* out) {
+    if (!q || !k || !v || !kv_lens || !out) return GQA_ERR_INVALID_ARG;
     if ((p->page_size != 0) != (block_table != nullptr)) return GQA_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return GQA_ERR_INVALID_ARG;
-    if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return GQA_ERR_INVALID_ARG;
     if (!mult8(p->q_stride_b) || !mult8(p->q_stride_h) || !mult8(p->k_stride_b) || !mult8(p->k_stride_h) ||
         !mult8(p->k_stride_t) || !mult8(p->v_stride_b) || !mult8(p->v_stride_h) || !mult8(p->v_stride_t))
         return GQA_ERR_INVALID_ARG;
     if (p->k_stride_t < gqa::kHeadDim || p->v_stride_t < gqa::kHeadDim || p->q_stride_h < gqa::kHeadDim)
         return GQA_ERR_INVALID_ARG;
+    return GQA_OK;
+}
+
+int run(const gqa_decode_params* p, const Plan& plan, const void* q, const void* k, const void* v,
+        const int32_t* kv_lens, const int32_t* block_table,
+        float* out, float* lse, void* workspace, size_t workspace_bytes, void* stream,
+        gqa_timer* timer) {
+    const int rc = check_tensors(p, q, k, v, kv_lens, block_table, out);
+    if (rc != GQA_OK) return rc;
+    if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return GQA_ERR_INVALID_ARG;
     if (workspace_bytes < plan.total_bytes()) return GQA_ERR_WORKSPACE_TOO_SMALL;
 
     KernelArgs a{};
@@ -137,12 +174,8 @@ int run(const gqa_decode_params* p, const void* q, const void* k, const void* v,
     a.v_stride_b = p->v_stride_b; a.v_stride_h = p->v_stride_h; a.v_stride_t = p->v_stride_t;
     a.scale_log2e = p->scale * 1.4426950408889634f;
 
-    int workgroups = workgroups_for(p->kernel_variant);
+    const int workgroups = launch_workgroups(p, plan.max_tiles);
     if (workgroups < 1) return GQA_ERR_LAUNCH;
-    // no more workgroups than the stream can feed with shares of the minimum length
-    const int per_group = p->kernel_variant == 1 ? 1 : gqa::partial_mfma_workers_per_group();
-    const int64_t useful = (plan.max_tiles + gqa::kMinShareTiles * per_group - 1) / (gqa::kMinShareTiles * per_group);
-    if (useful < workgroups) workgroups = (int)(useful > 0 ? useful : 1);
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipEvent_t* ev = nullptr;
@@ -177,6 +210,7 @@ const char* gqa_decode_strerror(int status) {
         case GQA_ERR_UNSUPPORTED: return "unsupported shape";
         case GQA_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
         case GQA_ERR_LAUNCH: return "HIP launch failed";
+        case GQA_ERR_SCRATCH_LIMIT: return "problem too large for the built-in scratch buffer";
         default: return "unknown status";
     }
 }
@@ -192,10 +226,8 @@ int gqa_decode_plan_info(const gqa_decode_params* params, const int32_t* host_kv
     Plan plan;
     const int rc = make_plan(params, &plan);
     if (rc != GQA_OK) return rc;
-    int wgs = workgroups_for(params->kernel_variant);      // 0 when no device is present
+    const int wgs = launch_workgroups(params, plan.max_tiles);     // 0 when no device is present
     const int per_group = params->kernel_variant == 1 ? 1 : gqa::partial_mfma_workers_per_group();
-    const int64_t useful = (plan.max_tiles + gqa::kMinShareTiles * per_group - 1) / (gqa::kMinShareTiles * per_group);
-    if (wgs > 0 && useful < wgs) wgs = (int)(useful > 0 ? useful : 1);
     if (workgroups) *workgroups = wgs;
     if (partial_slots) *partial_slots = plan.slots;
     if (share_tokens) {
@@ -214,20 +246,56 @@ int gqa_decode_plan_info(const gqa_decode_params* params, const int32_t* host_kv
     return GQA_OK;
 }
 
+int gqa_decode_init(void) {
+    if (workgroups_for(0) < 1 || workgroups_for(1) < 1) return GQA_ERR_LAUNCH;
+    if (gqa::prepare_prefill() != hipSuccess) return GQA_ERR_LAUNCH;
+    void* ptr = nullptr;
+    return static_scratch(&ptr);
+}
+
 int gqa_decode_attn(const gqa_decode_params* params, const void* q, const void* k, const void* v,
                     const int32_t* kv_lens, const int32_t* block_table, const int32_t* host_kv_lens,
                     float* out, float* lse, void* workspace, size_t workspace_bytes, void* stream) {
-    return run(params, q, k, v, kv_lens, block_table, host_kv_lens, out, lse, workspace,
-               workspace_bytes, stream, nullptr);
+    (void)host_kv_lens;      // the launch size does not depend on the lengths
+    Plan plan;
+    const int rc = make_plan(params, &plan);
+    if (rc != GQA_OK) return rc;
+    return run(params, plan, q, k, v, kv_lens, block_table, out, lse, workspace, workspace_bytes, stream, nullptr);
+}
+
+size_t gqa_decode_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int gqa_decode_attn_static(const gqa_decode_params* params, const void* q, const void* k, const void* v,
+                           const int32_t* kv_lens, const int32_t* block_table,
+                           float* out, float* lse, void* stream) {
+    // sized for the launch this device will really get, not for the largest one the library knows
+    Plan plan;
+    int rc = make_plan(params, &plan);
+    if (rc != GQA_OK) return rc;
+    rc = check_tensors(params, q, k, v, kv_lens, block_table, out);
+    if (rc != GQA_OK) return rc;
+    const int workgroups = launch_workgroups(params, plan.max_tiles);
+    if (workgroups < 1) return GQA_ERR_LAUNCH;
+    const int per_group = params->kernel_variant == 1 ? 1 : gqa::partial_mfma_workers_per_group();
+    rc = make_plan(params, &plan, (int64_t)workgroups * per_group);
+    if (rc != GQA_OK) return rc;
+    if (plan.total_bytes() > kStaticScratchBytes) return GQA_ERR_SCRATCH_LIMIT;
+    void* ptr = nullptr;
+    rc = static_scratch(&ptr);
+    if (rc != GQA_OK) return rc;
+    return run(params, plan, q, k, v, kv_lens, block_table, out, lse, ptr, kStaticScratchBytes, stream, nullptr);
 }
 
 int gqa_decode_attn_timed(const gqa_decode_params* params, const void* q, const void* k, const void* v,
                           const int32_t* kv_lens, const int32_t* block_table,
                           const int32_t* host_kv_lens, float* out, float* lse, void* workspace,
                           size_t workspace_bytes, void* stream, gqa_timer* timer) {
+    (void)host_kv_lens;
     if (timer == nullptr) return GQA_ERR_INVALID_ARG;
-    return run(params, q, k, v, kv_lens, block_table, host_kv_lens, out, lse, workspace,
-               workspace_bytes, stream, timer);
+    Plan plan;
+    const int rc = make_plan(params, &plan);
+    if (rc != GQA_OK) return rc;
+    return run(params, plan, q, k, v, kv_lens, block_table, out, lse, workspace, workspace_bytes, stream, timer);
 }
 
 int gqa_timer_create(int32_t max_calls, gqa_timer** host_out) {

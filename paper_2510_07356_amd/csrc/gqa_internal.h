@@ -221,6 +221,7 @@ struct PrefillArgs {
     float scale_log2e;
 };
 hipError_t launch_prefill(const PrefillArgs& a, hipStream_t s);
+hipError_t prepare_prefill();      // per-device set-up of the prefill kernel (idempotent)
 
 // Device-side view of one append call.
 struct AppendArgs {

@@ -33,6 +33,8 @@
 #include "gqa_internal.h"
 #include "gqa_mfma_tile.h"
 
+#include <atomic>
+
 namespace gqa {
 
 namespace {
@@ -343,12 +345,25 @@ constexpr size_t kPrefillLds = (size_t)(2 * kKTile + 2 * kVTile) * sizeof(uint16
 
 }  // namespace
 
+// More than the default 64 KB of LDS: the limit is a per-device attribute of the kernel, raised
+// once per device (gqa_decode_init, or the first prefill call on that device).
+hipError_t prepare_prefill() {
+    constexpr int kMaxDevices = 64;
+    static std::atomic<bool> done[kMaxDevices];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    if (done[dev].load(std::memory_order_acquire)) return hipSuccess;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)kPrefillLds);
+    if (e == hipSuccess) done[dev].store(true, std::memory_order_release);
+    return e;
+}
+
 hipError_t launch_prefill(const PrefillArgs& a, hipStream_t s) {
-    // more than the default 64 KB of LDS: the limit is a per-device attribute of the kernel, set on every
-    // launch (a few microseconds against milliseconds of kernel) so that each device a process uses has it
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)kPrefillLds) != hipSuccess)
-        return hipErrorInvalidValue;
+    const hipError_t ready = prepare_prefill();
+    if (ready != hipSuccess) return ready;
     const int n_qb = (a.seq_len + kBM - 1) / kBM;
     const int heads_per_xcd = (a.num_kv_heads + 7) / 8;
     const int64_t grid = 8LL * a.group * n_qb * heads_per_xcd * a.batch;
