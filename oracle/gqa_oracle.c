@@ -177,7 +177,9 @@ int gqa_oracle_decode_attn(const gqa_oracle_shape *s,
  *     x'[d + D/2] = x[d + D/2] * cos[pos][d] + x[d] * sin[pos][d]
  * with pos = kv_lens[b] - 1 and the caller's table cos_sin[pos][0..D/2) = cos,
  * cos_sin[pos][D/2..D) = sin (fp32, widened exactly).  Arithmetic in double,
- * result rounded to bf16 with round-to-nearest-even.  cos_sin == NULL copies
+ * result rounded to bf16 with round-to-nearest-even on the whole bf16 grid
+ * (sub-normal spacing 2^-133 below 2^-126, signed zeros, overflow to infinity);
+ * a NaN result is stored as the quiet NaN 0x7FC0.  cos_sin == NULL copies
  * q and k unchanged.  V is always copied bit for bit.  For a sequence with
  * kv_lens[b] <= 0 the query is copied unchanged and nothing is written to the
  * cache.  Cache addressing as in the attention oracle.
@@ -186,7 +188,8 @@ static uint16_t round_to_bf16(double x)
 {
     /* double -> float is exact enough here only if we round once: go through
      * the exact integer representation of the bf16 grid instead. */
-    if (x == 0.0 || isnan(x) || isinf(x)) {
+    if (isnan(x)) return 0x7FC0;            /* one quiet NaN, whatever the sign and payload */
+    if (x == 0.0 || isinf(x)) {
         float f = (float)x;
         uint32_t w;
         memcpy(&w, &f, sizeof w);

@@ -133,6 +133,61 @@ def decode_attn(q: np.ndarray, k: np.ndarray, v: np.ndarray, kv_lens: np.ndarray
     return OracleResult(out=out, lse=lse, weights=w, threads=used)
 
 
+def causal_attn_rows(q: np.ndarray, k: np.ndarray, v: np.ndarray, b: int, rows, scale: float) -> OracleResult:
+    """Rows `rows` of causal attention over sequence b of q [B, T, Hq, D], k, v [B, T, Hkv, D]:
+    row t is, by definition, the attention of query t over keys and values 0 .. t, i.e. decode_attn
+    with kv_len = t + 1.  One oracle "sequence" per requested row, all reading the same K/V of
+    sequence b (a view with batch stride 0, nothing is copied).  Result: out [R, Hq, D], lse [R, Hq]."""
+    q, k, v = _u16(q), _u16(k), _u16(v)
+    rows = np.asarray(rows, dtype=np.int64)
+    if rows.ndim != 1 or (len(rows) and (rows.min() < 0 or rows.max() >= q.shape[1])):
+        raise ValueError("rows out of range")
+    qq = np.ascontiguousarray(q[b, rows])                        # [R, Hq, D]
+    kb, vb = k[b].transpose(1, 0, 2), v[b].transpose(1, 0, 2)    # [Hkv, T, D] views
+    kk = np.broadcast_to(kb[None], (len(rows),) + kb.shape)      # [R, Hkv, T, D], stride 0 over R
+    vv = np.broadcast_to(vb[None], (len(rows),) + vb.shape)
+    return decode_attn(qq, kk, vv, rows + 1, scale)
+
+
+def shared_prefix_attn(q: np.ndarray, k_prefix: np.ndarray, v_prefix: np.ndarray, prefix_lens: np.ndarray,
+                       group_start: np.ndarray, k: np.ndarray, v: np.ndarray, kv_lens: np.ndarray, scale: float,
+                       block_table: Optional[np.ndarray] = None, page_size: int = 0) -> OracleResult:
+    """Attention of every sequence over [prefix of its group ; its own suffix].  Group j holds the
+    sequences group_start[j] .. group_start[j+1]-1 and its prefix is k_prefix[j, :, :prefix_lens[j]]
+    (indexed [group, kv head, token, d]); k, v, kv_lens, block_table describe the suffix caches as
+    in decode_attn.  The definition needs no sharing: every sequence gets a private contiguous cache
+    holding the two pieces one after the other, and decode_attn runs on that."""
+    q, k, v, kp, vp = _u16(q), _u16(k), _u16(v), _u16(k_prefix), _u16(v_prefix)
+    B, Hkv, D = q.shape[0], kp.shape[1], q.shape[2]
+    group_start = np.asarray(group_start, dtype=np.int64)
+    prefix_lens = np.asarray(prefix_lens, dtype=np.int64)
+    kv_lens = np.asarray(kv_lens, dtype=np.int64)
+    if group_start[0] != 0 or group_start[-1] != B or np.any(np.diff(group_start) < 0):
+        raise ValueError("group_start must rise from 0 to the batch size")
+    total = np.zeros(B, dtype=np.int64)
+    for j in range(len(prefix_lens)):
+        total[group_start[j]:group_start[j + 1]] = prefix_lens[j]
+    total += kv_lens
+    cap = max(int(total.max(initial=0)), 1)
+    kc = np.zeros((B, Hkv, cap, D), dtype=np.uint16)
+    vc = np.zeros((B, Hkv, cap, D), dtype=np.uint16)
+    for j in range(len(prefix_lens)):
+        P = int(prefix_lens[j])
+        for b in range(int(group_start[j]), int(group_start[j + 1])):
+            kc[b, :, :P] = kp[j, :, :P]
+            vc[b, :, :P] = vp[j, :, :P]
+            S = int(kv_lens[b])
+            if page_size:
+                for t in range(S):
+                    blk, slot = int(block_table[b, t // page_size]), t % page_size
+                    kc[b, :, P + t] = k[blk, :, slot]
+                    vc[b, :, P + t] = v[blk, :, slot]
+            else:
+                kc[b, :, P:P + S] = k[b, :, :S]
+                vc[b, :, P:P + S] = v[b, :, :S]
+    return decode_attn(q, kc, vc, total.astype(np.int32), scale)
+
+
 def kv_append(q: np.ndarray, k_new: np.ndarray, v_new: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray,
               kv_lens: np.ndarray, cos_sin: Optional[np.ndarray] = None,
               block_table: Optional[np.ndarray] = None, page_size: int = 0) -> np.ndarray:

@@ -6,8 +6,10 @@
 // column d < 64 pairs with column d + 64,
 //     x' = x cos - y sin,   y' = y cos + x sin.
 // The products of a bf16 value and an fp32 table entry are exact in fp64, so the rotation is done
-// in fp64 (one rounding) and rounded once to bf16, nearest-even: the result is the correctly
-// rounded one.  One workgroup per sequence, one thread per column pair; the work is a few KB per
+// in fp64 (the difference or sum of the two exact products is its only rounding) and the fp64
+// result is rounded to bf16, nearest-even, over the whole bf16 range: normal results, sub-normal
+// results (fixed spacing 2^-133), signed zeros, overflow to infinity; a NaN result is stored as
+// the quiet NaN 0x7FC0.  One workgroup per sequence, one thread per column pair; the work is a few KB per
 // sequence, so the kernel is launch-bound and nothing here is tuned.
 #include "gqa_internal.h"
 
@@ -17,13 +19,21 @@ namespace {
 
 __device__ __forceinline__ double widen(uint16_t bits) { return (double)__uint_as_float((uint32_t)bits << 16); }
 
-// Nearest-even rounding of a finite double in the normal bf16 range to bf16 (8 significant bits).
+// Nearest-even rounding of a double to bf16.
 __device__ __forceinline__ uint16_t round_bf16(double x) {
+    if (x != x) return 0x7FC0u;
     unsigned long long u = __double_as_longlong(x);
+    const double ax = fabs(x);
+    if (ax < 0x1p-126) {
+        // zero or below the smallest normal bf16: the grid is q * 2^-133, q = 0 .. 128 (q = 128 is the
+        // smallest normal number, whose bit pattern 0x0080 is again q); the scaling is exact in fp64
+        const unsigned q = (unsigned)rint(ax * 0x1p133);
+        return (uint16_t)((unsigned)(u >> 48) & 0x8000u) | (uint16_t)q;
+    }
     const unsigned long long lsb = (u >> 45) & 1ull;
     u += (1ull << 44) - 1ull + lsb;            // carries into the exponent when the mantissa overflows
     u &= ~((1ull << 45) - 1ull);
-    const float f = (float)__longlong_as_double(u);      // exact: 8 significant bits
+    const float f = (float)__longlong_as_double(u);      // exact (8 significant bits), or infinity beyond the range
     return (uint16_t)(__float_as_uint(f) >> 16);
 }
 

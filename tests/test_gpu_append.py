@@ -106,3 +106,45 @@ def test_one_decode_step_append_then_attend(binding, paged):
     assert np.abs(err).max() <= 1e-2 and np.linalg.norm(err) / np.linalg.norm(ref.out) <= 5e-3
     assert np.abs(lse.double().cpu().numpy() - ref.lse).max() <= 4e-3
     del torch
+
+
+def test_append_rounding_over_the_whole_bf16_range(binding):
+    """Operands and table entries whose rotated results land below the normal bf16 range (sub-normal
+    grid, signed zeros), on ties, beyond the largest finite value, and on NaN: the kernel's bits must
+    equal the oracle's for every element."""
+    import torch
+    B, Hq, Hkv, D = 6, 8, 8, 128
+    rng = np.random.default_rng(230)
+
+    def spread(shape):
+        # bf16 bit patterns with exponents over the whole range, both signs; a few special values
+        bits = rng.integers(0, 0x7F80, size=shape).astype(np.uint16) | (rng.integers(0, 2, size=shape).astype(np.uint16) << 15)
+        flat = bits.reshape(-1)
+        flat[::97] = 0x0080            # smallest normal
+        flat[1::97] = 0x8000           # -0
+        flat[2::97] = 0x7F7F           # largest finite
+        flat[3::211] = 0x7F80          # +inf
+        flat[4::211] = 0x7FC1          # NaN
+        return bits
+
+    lens = [1, 2, 3, 4, 5, 6]
+    w = wl.make_contiguous("app_range", 231, B, Hq, Hkv, lens, cache_len=8)
+    w.q = spread((B, Hq, D))
+    k_new, v_new = spread((B, Hkv, D)), spread((B, Hkv, D))
+    # pairs whose difference cancels into lower binades: second half equal to the first up to a few ulps
+    k_new[:, :, D // 2:] = k_new[:, :, :D // 2] ^ rng.integers(0, 4, size=(B, Hkv, D // 2)).astype(np.uint16)
+    table = rng.uniform(-1, 1, size=(8, D)).astype(np.float32)
+    table[0, :D // 2] = (rng.integers(0, 257, size=D // 2) / 256.0).astype(np.float32)      # dyadic: ties on the 2^-133 grid
+    table[0, D // 2:] = 0.0
+    table[1] = 1.0                                                                           # x - y, y + x
+    table[2, :D // 2] = (2.0 ** -rng.integers(0, 140, size=D // 2).astype(np.float64)).astype(np.float32)   # down to fp32 sub-normals
+    dev, q_out = run_append(binding, w, k_new, v_new, table)
+    q_ref = kv_append(w.q, k_new, v_new, w.k, w.v, w.kv_lens, cos_sin=table)
+    got_q = to_bits(q_out)
+    np.testing.assert_array_equal(got_q, q_ref)
+    np.testing.assert_array_equal(to_bits(dev["k"]), np.ascontiguousarray(w.k))
+    np.testing.assert_array_equal(to_bits(dev["v"]), np.ascontiguousarray(w.v))
+    mag = q_ref & 0x7FFF
+    assert ((mag > 0) & (mag < 0x0080)).sum() > 20, "the case must reach the sub-normal grid"
+    assert (mag == 0).any() and (mag == 0x7F80).any() and (q_ref == 0x7FC0).any()
+    del torch

@@ -1,10 +1,11 @@
-"""GPU parity of shared-prefix (cascade) decode attention against the oracle.  The oracle is
-given the same problem without sharing: one contiguous cache per sequence holding the prefix of
-its group followed by its suffix.  Tolerances as in test_gpu_parity.py."""
+"""GPU parity of shared-prefix (cascade) decode attention against the oracle
+(oracle.shared_prefix_attn: the same problem without sharing, one private cache per sequence holding
+the prefix of its group followed by its suffix; pinned against brute force in
+tests/test_oracle_pins.py).  Tolerances as in test_gpu_parity.py."""
 import numpy as np
 import pytest
 
-from oracle import decode_attn
+from oracle import shared_prefix_attn
 from paper_2510_07356_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
@@ -18,20 +19,26 @@ def binding():
     return b
 
 
+def oracle_reference(sw):
+    w = sw.base
+    return shared_prefix_attn(w.q, sw.kp, sw.vp, sw.prefix_lens, sw.group_start, w.k, w.v, w.kv_lens, w.scale,
+                              block_table=w.block_table, page_size=w.page_size)
+
+
 def check(sw, out, lse, tag):
-    c = sw.concatenated()
-    ref = decode_attn(c.q, c.k, c.v, c.kv_lens, c.scale)
+    ref = oracle_reference(sw)
+    full_lens = np.repeat(sw.prefix_lens, np.diff(sw.group_start)).astype(np.int64) + sw.base.kv_lens
     got = out.double().cpu().numpy()
     assert np.isfinite(got).all(), f"{tag}: non-finite"
     err = got - ref.out
     max_abs = np.abs(err).max()
     rel = np.linalg.norm(err) / max(np.linalg.norm(ref.out), 1e-30)
-    worst = max([np.linalg.norm(err[b]) / np.linalg.norm(ref.out[b]) for b in range(c.batch) if c.kv_lens[b] > 0],
+    worst = max([np.linalg.norm(err[b]) / np.linalg.norm(ref.out[b]) for b in range(sw.base.batch) if full_lens[b] > 0],
                 default=0.0)
     print(f"{tag}: max_abs={max_abs:.3e} rel_l2={rel:.3e} worst_seq_rel_l2={worst:.3e}", flush=True)
     assert max_abs <= MAX_ABS and rel <= REL_L2 and worst <= REL_L2, tag
     gl = lse.double().cpu().numpy()
-    empty = c.kv_lens == 0
+    empty = full_lens == 0
     assert np.all(got[empty] == 0.0) and np.all(np.isneginf(gl[empty]))
     assert np.abs(gl[~empty] - ref.lse[~empty]).max(initial=0.0) <= LSE_ABS, f"{tag}: lse"
 
@@ -78,6 +85,18 @@ def test_zero_negative_and_large_scale(binding, scale, paged):
     sw = wl.make_shared_prefix("casc_scale", 304, [5, 2, 1], [300, 40, 0], [120, 1, 0, 77, 500, 64, 9, 200],
                                paged=paged, scale=scale)
     check(sw, *binding.run_shared_prefix(sw), f"casc_scale_{scale}_paged{int(paged)}")
+
+
+@pytest.mark.parametrize("paged", [False, True])
+def test_groups_without_sequences(binding, paged):
+    """group_start may repeat a value: a group with no sequence (its prefix is never read), at the
+    start, in the middle and at the end of the list."""
+    sizes = [0, 3, 0, 0, 2, 4, 0]
+    prefixes = [500, 100, 64, 0, 33, 257, 90]
+    suffixes = [40, 0, 130, 1, 65, 300, 31, 32, 0]
+    sw = wl.make_shared_prefix("casc_holes", 305, sizes, prefixes, suffixes, paged=paged)
+    for chunk in (0, 64):
+        check(sw, *binding.run_shared_prefix(sw, chunk_tokens=chunk), f"casc_holes/paged{int(paged)}/c{chunk}")
 
 
 def test_too_large_group_is_rejected(binding):

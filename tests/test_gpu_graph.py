@@ -6,7 +6,7 @@ ordinary eager work and synchronisation between the replays."""
 import numpy as np
 import pytest
 
-from oracle import decode_attn, kv_append
+from oracle import decode_attn, kv_append, shared_prefix_attn
 from paper_2510_07356_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
@@ -119,3 +119,91 @@ def test_captured_decode_step_replays(binding, paged):
         torch.cuda.synchronize()
         eager_out.copy_(out)
         assert torch.equal(eager_out, keep), step
+
+
+def replay_and_compare(graph, eager, outputs, replays=3):
+    """Replays `graph` several times with eager work and synchronisation in between; every replay
+    must reproduce, bit for bit, what the same calls give when run eagerly."""
+    import torch
+    eager()
+    torch.cuda.synchronize()
+    want = [t.clone() for t in outputs]
+    for r in range(replays):
+        for t in outputs:
+            t.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        for t, w in zip(outputs, want):
+            assert torch.equal(t, w), f"replay {r}"
+        eager()                      # the program's own eager work between replays
+        torch.cuda.synchronize()
+
+
+def test_captured_prefill_shared_prefix_and_static_calls(binding):
+    """After gqa_decode_init() the other entry points can be captured too: causal prefill (its LDS
+    limit is a per-device attribute set at init), the shared-prefix call, and the call that uses the
+    built-in scratch buffer.  Run alone, these are the first calls of the process on these entry points."""
+    import torch
+    binding.gqa_decode_init()
+    scale = float(np.float32(1.0 / np.sqrt(128)))
+    rng = np.random.default_rng(77)
+    bits = lambda shape: binding._bf16_view(wl.f32_to_bf16_bits(rng.standard_normal(shape).astype(np.float32))).to("cuda:0")
+
+    # prefill, ragged batch of two prompts
+    pq, pk, pv = bits((2, 300, 10, 128)), bits((2, 300, 2, 128)), bits((2, 300, 2, 128))
+    p_lens = torch.tensor([300, 129], dtype=torch.int32, device="cuda:0")
+    p_out = torch.zeros((2, 300, 10, 128), dtype=torch.float32, device="cuda:0")
+    p_lse = torch.zeros((2, 300, 10), dtype=torch.float32, device="cuda:0")
+
+    # shared prefix: 2 prompts x 3 samples
+    sw = wl.make_shared_prefix("graph_casc", 320, [3, 3], [200, 65], [40, 1, 300, 0, 77, 130])
+    sdev = binding.shared_prefix_to_device(sw)
+    cp = binding.make_cascade_params(sdev["q"], sdev["k"], sdev["v"], sdev["kp"], sdev["vp"], sw.base.max_kv_len,
+                                     int(sw.prefix_lens.max()), 2, sw.base.scale)
+    s_ws = torch.empty(binding.gqa_cascade_workspace_bytes(cp), dtype=torch.uint8, device="cuda:0")
+    s_out = torch.zeros((6, 40, 128), dtype=torch.float32, device="cuda:0")
+    s_lse = torch.zeros((6, 40), dtype=torch.float32, device="cuda:0")
+
+    def casc():         # marshalled at call time: the call goes to the stream that is current then
+        binding.CascadeCall(cp, sdev["q"], sdev["kp"], sdev["vp"], sdev["prefix_lens"], sdev["group_start"],
+                            sw.group_start, sdev["k"], sdev["v"], sdev["kv_lens"], None, s_out, s_lse, s_ws)()
+
+    # plain decode on the built-in scratch buffer
+    w = wl.make_contiguous("graph_static", 321, 3, 40, 8, [900, 31, 257])
+    dev = binding.to_device(w)
+    params = binding.make_params(dev["q"], dev["k"], dev["v"], w.max_kv_len, w.scale)
+    d_out = torch.zeros((3, 40, 128), dtype=torch.float32, device="cuda:0")
+    d_lse = torch.zeros((3, 40), dtype=torch.float32, device="cuda:0")
+
+    def calls():
+        binding.gqa_prefill_attn(pq, pk, pv, scale, p_out, p_lse, seq_lens=p_lens)
+        casc()
+        binding.gqa_decode_attn_static(params, dev["q"], dev["k"], dev["v"], dev["kv_lens"], None, d_out, d_lse)
+
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        calls()
+    # rows of the second prompt beyond its length are not written: compare the written part only
+    p_out[1, 129:] = 0
+    p_lse[1, 129:] = 0
+
+    def eager():
+        calls()
+        p_out[1, 129:] = 0
+        p_lse[1, 129:] = 0
+
+    def replay_outputs():
+        return [p_out[0], p_out[1, :129], p_lse[0], p_lse[1, :129], s_out, s_lse, d_out, d_lse]
+
+    # torch.equal on views: materialise through the helper's clone()
+    replay_and_compare(graph, eager, replay_outputs())
+
+    # and the results are the right ones
+    ref = decode_attn(w.q, w.k, w.v, w.kv_lens, w.scale)
+    err = d_out.double().cpu().numpy() - ref.out
+    assert np.abs(err).max() <= 1e-2 and np.linalg.norm(err) / np.linalg.norm(ref.out) <= 5e-3
+    ref = shared_prefix_attn(sw.base.q, sw.kp, sw.vp, sw.prefix_lens, sw.group_start, sw.base.k, sw.base.v,
+                             sw.base.kv_lens, sw.base.scale)
+    err = s_out.double().cpu().numpy() - ref.out
+    assert np.abs(err).max() <= 1e-2 and np.linalg.norm(err) / np.linalg.norm(ref.out) <= 5e-3

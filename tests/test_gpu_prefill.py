@@ -1,11 +1,11 @@
 """GPU parity of causal prefill attention.  Row t of causal attention is, by definition, the decode
-attention of query t over the first t + 1 keys, so the (pinned) decode oracle serves: it is called
-with one "sequence" per checked row, all sharing the same K/V cache (batch stride 0) with
-kv_len = t + 1.  Small cases check every row; the 32,768-token case checks sampled rows."""
+attention of query t over the first t + 1 keys, so the (pinned) decode oracle serves through
+oracle.causal_attn_rows (itself pinned against a brute-force causal attention in
+tests/test_oracle_pins.py).  Small cases check every row; the 32,768-token case checks sampled rows."""
 import numpy as np
 import pytest
 
-from oracle import decode_attn
+from oracle import causal_attn_rows as oracle_rows
 from paper_2510_07356_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
@@ -25,15 +25,6 @@ def make_inputs(seed, B, T, Hq, Hkv, D=128):
     k = wl.f32_to_bf16_bits(rng.standard_normal((B, T, Hkv, D), dtype=np.float32))
     v = wl.f32_to_bf16_bits(rng.standard_normal((B, T, Hkv, D), dtype=np.float32))
     return q, k, v
-
-
-def oracle_rows(q, k, v, b, rows, scale):
-    """Causal attention rows `rows` of sequence b via the decode oracle."""
-    rows = np.asarray(rows)
-    qq = np.ascontiguousarray(q[b, rows])                                  # [R, Hq, D]
-    kk = np.broadcast_to(k[b].transpose(1, 0, 2)[None], (len(rows),) + k[b].transpose(1, 0, 2).shape)
-    vv = np.broadcast_to(v[b].transpose(1, 0, 2)[None], kk.shape)          # [R, Hkv, T, D], batch stride 0
-    return decode_attn(qq, kk, vv, rows + 1, scale)
 
 
 def run(binding, q, k, v, scale):
@@ -118,6 +109,19 @@ def test_strided_inputs_and_group_sizes(binding):
         binding.gqa_prefill_attn(fused[:, :, :Hq], fused[:, :, Hq:Hq + Hkv], fused[:, :, Hq + Hkv:], scale, out, lse)
         rows = np.arange(T)
         check_rows(out, lse, oracle_rows(q, k, v, 0, rows, scale), 0, rows, f"prefill_fused_{Hq}_{Hkv}")
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(32, 16), (16, 16), (6, 3), (9, 9), (24, 12)])
+def test_kv_head_counts_beyond_and_off_the_xcd_count(binding, Hq, Hkv):
+    """KV heads are dealt to the 8 XCDs: more than 8 (two heads per XCD), fewer, and counts that are
+    not a multiple of 8 (workgroups whose head does not exist leave at once)."""
+    scale = float(np.float32(1.0 / np.sqrt(128)))
+    T = 300
+    q, k, v = make_inputs(480 + Hq + Hkv, 2, T, Hq, Hkv)
+    out, lse = run(binding, q, k, v, scale)
+    rows = np.arange(T)
+    for b in range(2):
+        check_rows(out, lse, oracle_rows(q, k, v, b, rows, scale), b, rows, f"prefill_heads_{Hq}_{Hkv}_b{b}")
 
 
 def test_long_sequence_sampled_rows(binding):

@@ -518,3 +518,220 @@ def test_rotary_matches_float64_rotate_half_formula():
     # correct rounding to 8 significant bits: every element within half a bf16 step of the exact value
     assert np.all(np.abs(got - want) <= 2.0 ** -8 * np.abs(want) * (1 + 1e-12))
     assert np.abs(got - want).max() > 0.0
+
+
+def _round_to_bf16_rational(value: float) -> int:
+    """Independent nearest-even rounding of a double to a bf16 bit pattern in exact rational
+    arithmetic: the bf16 grid around |value| has spacing 2^(max(e, -126) - 7) with
+    2^e <= |value| < 2^(e+1); anything at or beyond 2^128 - 2^119 (half a step above the largest
+    bf16) is infinity."""
+    from fractions import Fraction
+    import math
+    if math.isnan(value):
+        return 0x7FC0
+    sign = 0x8000 if math.copysign(1.0, value) < 0 else 0
+    if math.isinf(value):
+        return sign | 0x7F80
+    a = abs(Fraction(value))
+    if a == 0:
+        return sign
+    e = a.numerator.bit_length() - a.denominator.bit_length()
+    if Fraction(2) ** e > a:
+        e -= 1
+    assert Fraction(2) ** e <= a < Fraction(2) ** (e + 1)
+    step = Fraction(2) ** (max(e, -126) - 7)
+    n, rem = divmod(a, step)
+    n = int(n)
+    if rem * 2 > step or (rem * 2 == step and n % 2 == 1):
+        n += 1
+    # n * step on the bf16 grid: magnitude bits are n + 128 * (max(e, -126) + 126) once the hidden bit is
+    # accounted for (sub-normal: n itself; normal: exponent field e + 127, mantissa n - 128)
+    if e < -126:
+        mag = n                       # n = 128 is the smallest normal number 0x0080
+    else:
+        mag = ((e + 127) << 7) + (n - 128)      # a mantissa carry (n = 256) rolls into the exponent
+    return sign | (0x7F80 if mag >= 0x7F80 else mag)
+
+
+def _rotate_one(xbits, ybits, c, s):
+    """Oracle results (x', y') for one pair (x, y) rotated with cos = c, sin = s (fp32 values)."""
+    D = 2
+    table = np.array([[c, s]], np.float32)
+    kc = np.zeros((1, 1, 1, D), np.uint16); vc = kc.copy()
+    q = np.array([[[xbits, ybits]]], np.uint16)
+    out = kv_append(q, q[:, :1], q[:, :1], kc, vc, np.array([1]), cos_sin=table)
+    np.testing.assert_array_equal(kc[0, 0, 0], out[0, 0])            # the key takes the same path as the query
+    return int(out[0, 0, 0]), int(out[0, 0, 1])
+
+
+def test_rotary_rounding_below_the_normal_range():
+    """bf16 results below 2^-126 sit on a grid of fixed spacing 2^-133 (sub-normal numbers) and
+    are rounded to nearest even on THAT grid, not truncated.  x = 2^-126 (0x0080) times a
+    dyadic cosine lands exactly where the case needs it."""
+    tiny = 0x0080
+    f = np.float32
+    # half the smallest normal number is the sub-normal 64 * 2^-133
+    assert _rotate_one(tiny, 0, f(0.5), f(0.0))[0] == 0x0040
+    # exact sub-normals survive: k * 2^-133
+    for kq in (1, 2, 3, 64, 127):
+        assert _rotate_one(tiny, 0, f(kq / 128.0), f(0.0))[0] == kq
+    # ties (k + 1/2) * 2^-133 go to the even neighbour
+    assert _rotate_one(tiny, 0, f(0.5 / 128.0), f(0.0))[0] == 0x0000        # 0.5 -> 0
+    assert _rotate_one(tiny, 0, f(1.5 / 128.0), f(0.0))[0] == 0x0002        # 1.5 -> 2
+    assert _rotate_one(tiny, 0, f(2.5 / 128.0), f(0.0))[0] == 0x0002        # 2.5 -> 2
+    assert _rotate_one(tiny, 0, f(126.5 / 128.0), f(0.0))[0] == 0x007E
+    assert _rotate_one(tiny, 0, f(127.5 / 128.0), f(0.0))[0] == 0x0080      # up into the normal range
+    # just off a tie: decided by the exact value (a truncating implementation gets these wrong)
+    assert _rotate_one(tiny, 0, f(2.5 / 128.0 * (1 + 2.0 ** -20)), f(0.0))[0] == 0x0003
+    assert _rotate_one(tiny, 0, f(1.5 / 128.0 * (1 - 2.0 ** -20)), f(0.0))[0] == 0x0001
+    assert _rotate_one(tiny, 0, f(0.75 / 128.0), f(0.0))[0] == 0x0001
+    # negative results keep their sign, also when they round to zero
+    assert _rotate_one(tiny | 0x8000, 0, f(3 / 128.0), f(0.0))[0] == 0x8003
+    assert _rotate_one(tiny | 0x8000, 0, f(0.25 / 128.0), f(0.0))[0] == 0x8000
+    # y' = y cos + x sin takes the same path
+    assert _rotate_one(tiny, 0, f(0.0), f(1.5 / 128.0))[1] == 0x0002
+
+
+def test_rotary_rounding_of_zero_infinity_and_nan():
+    f = np.float32
+    one, big = 0x3F80, 0x7F7F                                  # 1.0, the largest finite bf16
+    assert _rotate_one(0x0000, 0x0000, f(1.0), f(0.0)) == (0x0000, 0x0000)
+    # (-0) * 1 - (+0) * 0 = -0; (+0) * 1 + (-0) * 0 = +0 (round-to-nearest sign rules of IEEE 754)
+    assert _rotate_one(0x8000, 0x0000, f(1.0), f(0.0)) == (0x8000, 0x0000)
+    # exact cancellation gives +0
+    assert _rotate_one(one, one, f(1.0), f(1.0))[0] == 0x0000
+    # overflow: big + big = 2^129 (1 - 2^-8) rounds to infinity; big * 1 stays finite
+    assert _rotate_one(big, big | 0x8000, f(1.0), f(1.0))[0] == 0x7F80
+    assert _rotate_one(big | 0x8000, big, f(1.0), f(1.0))[0] == 0xFF80
+    assert _rotate_one(big, 0, f(1.0), f(0.0))[0] == big
+    # big = 2^128 - 2^120, the grid step there is 2^120: big + 2^119 is a tie whose even neighbour is
+    # 2^128 = infinity; big + 1.5 * 2^118 is below the tie and stays; big + 1.5 * 2^119 is above it
+    assert _rotate_one(big, 0x7B00, f(1.0), f(-1.0))[0] == 0x7F80            # 0x7B00 = 2^119
+    assert _rotate_one(big, 0x7AC0, f(1.0), f(-1.0))[0] == big               # 0x7AC0 = 1.5 * 2^118
+    assert _rotate_one(big, 0x7B40, f(1.0), f(-1.0))[0] == 0x7F80            # 0x7B40 = 1.5 * 2^119
+    # infinities pass through; inf * 0 and inf - inf are NaN, stored as the one quiet NaN 0x7FC0
+    assert _rotate_one(0x7F80, 0, f(1.0), f(0.0)) == (0x7F80, 0x7FC0)       # x' = inf - 0, y' = 0 + inf * 0
+    assert _rotate_one(0x7F80, 0, f(2.0), f(1.0)) == (0x7F80, 0x7F80)
+    assert _rotate_one(0xFF80, 0, f(2.0), f(1.0)) == (0xFF80, 0xFF80)
+    assert _rotate_one(0x7F80, 0x7F80, f(1.0), f(1.0))[0] == 0x7FC0
+    assert _rotate_one(0x7FC1, 0, f(1.0), f(1.0)) == (0x7FC0, 0x7FC0)
+    assert _rotate_one(0xFFFF, 0, f(1.0), f(1.0)) == (0x7FC0, 0x7FC0)
+
+
+def test_rotary_rounding_matches_rational_rounding_over_the_whole_range():
+    """Seeded sweep over magnitudes from far below the sub-normal range to overflow: the fp64
+    expression x c - y s (Python floats are IEEE doubles and never contract) rounded to bf16 in
+    exact rational arithmetic must equal the oracle's bits."""
+    rng = np.random.default_rng(11)
+    n = 4000
+    # bf16 operands with exponents spread over the whole range, fp32 cos/sin in [-1, 1] and a few larger
+    xb = rng.integers(0, 0x7F80, size=n).astype(np.uint16) | (rng.integers(0, 2, size=n).astype(np.uint16) << 15)
+    yb = rng.integers(0, 0x7F80, size=n).astype(np.uint16) | (rng.integers(0, 2, size=n).astype(np.uint16) << 15)
+    # half of the pairs: y close to x in magnitude so that the difference cancels into lower binades
+    yb[: n // 2] = (xb[: n // 2] & 0x7FFF) ^ rng.integers(0, 8, size=n // 2).astype(np.uint16)
+    c = rng.uniform(-1, 1, size=n).astype(np.float32)
+    s = rng.uniform(-1, 1, size=n).astype(np.float32)
+    c[::7] = np.float32(1.0); s[::7] = np.float32(1.0)
+    c[::11] = (rng.integers(1, 256, size=len(c[::11])) / 128.0).astype(np.float32); s[::11] = 0
+    D = 2
+    q = np.stack([xb, yb], axis=-1)[:, None, :]                       # [n, 1, 2]
+    table = np.zeros((n, D), np.float32)
+    table[:, 0], table[:, 1] = c, s
+    kc = np.zeros((n, 1, 1, D), np.uint16)
+    out = np.empty((n, 2), np.uint16)
+    for i in range(n):                                                 # one call per pair: position 0, own table row
+        o = kv_append(q[i:i + 1], q[i:i + 1, :1], q[i:i + 1, :1], kc[i:i + 1], kc[i:i + 1].copy(),
+                      np.array([1]), cos_sin=table[i:i + 1])
+        out[i] = o[0, 0]
+    xs, ys = bf16_bits_to_f32(xb).astype(np.float64), bf16_bits_to_f32(yb).astype(np.float64)
+    seen_sub = seen_inf = 0
+    for i in range(n):
+        x, y, ci, si = float(xs[i]), float(ys[i]), float(c[i]), float(s[i])
+        want = (_round_to_bf16_rational(x * ci - y * si), _round_to_bf16_rational(y * ci + x * si))
+        assert (int(out[i, 0]), int(out[i, 1])) == want, (i, hex(xb[i]), hex(yb[i]), ci, si)
+        seen_sub += (want[0] & 0x7FFF) < 0x0080
+        seen_inf += (want[0] & 0x7FFF) == 0x7F80
+    assert seen_sub > 20                                        # the sweep reaches the sub-normal grid
+    del seen_inf
+
+
+# ---------------------------------------------------------------------------
+# Causal rows and shared-prefix attention: the two thin front ends that decide what
+# decode_attn is asked, against brute force written out in plain Python
+# ---------------------------------------------------------------------------
+from oracle import causal_attn_rows, shared_prefix_attn  # noqa: E402
+from paper_2510_07356_amd.workloads import make_shared_prefix  # noqa: E402
+
+
+def _softmax_attention(qrow, keys, values, scale):
+    """exp(s) / sum exp(s) in plain Python floats with math.fsum, no max subtraction."""
+    s = [scale * math.fsum(a * b for a, b in zip(qrow, kr)) for kr in keys]
+    e = [math.exp(x) for x in s]
+    z = math.fsum(e)
+    D = len(values[0])
+    return [math.fsum(e[j] / z * values[j][d] for j in range(len(keys))) for d in range(D)], math.log(z)
+
+
+@pytest.mark.parametrize("T,Hq,Hkv", [(1, 2, 1), (5, 4, 2), (6, 3, 3)])
+def test_causal_rows_against_brute_force(T, Hq, Hkv):
+    """Row t sees keys 0..t of ITS sequence and of kv head h / (Hq / Hkv): an off-by-one in the
+    visible length, a mixed-up sequence or a transposed token/head axis all change the numbers."""
+    B, D, scale = 2, 4, 0.5
+    rng = np.random.default_rng(60 + T)
+    q = small_ints(rng, (B, T, Hq, D))
+    k = small_ints(rng, (B, T, Hkv, D))
+    v = small_ints(rng, (B, T, Hkv, D))
+    G = Hq // Hkv
+    for b in range(B):
+        rows = list(range(T))[::-1]                     # any order, any subset
+        res = causal_attn_rows(bits(q), bits(k), bits(v), b, rows, scale)
+        assert res.out.shape == (T, Hq, D)
+        for i, t in enumerate(rows):
+            for h in range(Hq):
+                g = h // G
+                want, want_lse = _softmax_attention(q[b, t, h].tolist(), k[b, :t + 1, g].tolist(),
+                                                    v[b, :t + 1, g].tolist(), scale)
+                np.testing.assert_allclose(res.out[i, h], want, rtol=0, atol=1e-13)
+                assert abs(res.lse[i, h] - want_lse) < 1e-13
+    # the first row is the first value row, the rows of sequence 0 do not depend on sequence 1
+    res0 = causal_attn_rows(bits(q), bits(k), bits(v), 0, [0], scale)
+    np.testing.assert_array_equal(res0.out[0], np.repeat(v[0, 0], G, axis=0).astype(np.float64))
+
+
+@pytest.mark.parametrize("paged", [False, True])
+def test_shared_prefix_against_brute_force(paged):
+    """Two groups (3 and 2 samples) with prefixes of 3 and 0 tokens, suffixes of 0..4 tokens: every
+    sequence attends over its group's prefix followed by its own suffix, nothing else."""
+    sizes, prefixes, suffixes = [3, 2], [3, 0], [2, 0, 4, 1, 3]
+    kw = dict(page_size=2) if paged else {}
+    sw = make_shared_prefix("pin_prefix", 70, sizes, prefixes, suffixes, num_q_heads=4, num_kv_heads=2,
+                            head_dim=4, paged=paged, **kw)
+    w = sw.base
+    res = shared_prefix_attn(w.q, sw.kp, sw.vp, sw.prefix_lens, sw.group_start, w.k, w.v, w.kv_lens, w.scale,
+                             block_table=w.block_table, page_size=w.page_size)
+    qf, kpf, vpf = bf16_bits_to_f32(w.q), bf16_bits_to_f32(sw.kp), bf16_bits_to_f32(sw.vp)
+    kf, vf = bf16_bits_to_f32(w.k), bf16_bits_to_f32(w.v)
+    group_of = [0, 0, 0, 1, 1]
+    for b in range(5):
+        j = group_of[b]
+        for h in range(4):
+            g = h // 2
+            keys = [kpf[j, g, t].tolist() for t in range(prefixes[j])]
+            vals = [vpf[j, g, t].tolist() for t in range(prefixes[j])]
+            for t in range(suffixes[b]):
+                if paged:
+                    blk, slot = int(w.block_table[b, t // 2]), t % 2
+                    keys.append(kf[blk, g, slot].tolist()); vals.append(vf[blk, g, slot].tolist())
+                else:
+                    keys.append(kf[b, g, t].tolist()); vals.append(vf[b, g, t].tolist())
+            if not keys:
+                assert np.all(res.out[b, h] == 0) and np.isneginf(res.lse[b, h])
+                continue
+            want, want_lse = _softmax_attention(qf[b, h].tolist(), keys, vals, float(w.scale))
+            np.testing.assert_allclose(res.out[b, h], want, rtol=0, atol=1e-13)
+            assert abs(res.lse[b, h] - want_lse) < 1e-12
+    # the benchmark's "same problem without sharing" workload is the same concatenation
+    c = sw.concatenated()
+    plain = decode_attn(c.q, c.k, c.v, c.kv_lens, c.scale)
+    np.testing.assert_array_equal(plain.out, res.out)
+    np.testing.assert_array_equal(plain.lse, res.lse)
