@@ -4,13 +4,19 @@
 A step is one gqa_decode_attn call (split-KV partial + combine kernels)
 on the ragged long-trace batch: B=64, Hq=40, Hkv=8, D=128, KV lengths uniform
 on [1024, 16384], head-major bf16 cache, inputs resident in HBM.  Calls
-alternate between two copies of the cache so that no call finds the previous
+alternate between copies of the cache so that no call finds the previous
 call's data in a cache.
 
 Prints one JSON line: metric = KV bytes streamed per second (TB/s), with the
 HBM roofline of the split-KV partial kernel (per-kernel time from HIP events
 recorded inside the timed region) and the fp64 CPU oracle timed on the host
-cores of the same machine.
+cores of the same machine.  After these headline keys (timed with exactly
+--steps / --warmup) the same line carries, from the same run:
+  per_config     all five named configurations (time, TB/s, kernel times, parity, oracle time)
+  prefill        causal prefill at 32,768 tokens and on a ragged prompt batch
+  shared_prefix  shared-prefix decode at 5 and 10 samples per prompt
+--config N times one configuration only (what the rocprofv3 summaries under profiles/ use);
+--no-extras prints the headline keys only.
 """
 import argparse
 import json
@@ -24,6 +30,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published peak
 EVENT_STRIDE = 4            # one step in four records HIP events around its kernels
+HEADLINE_CONFIG = 2         # the 16K-token ragged batch the target is quoted on
 
 
 PARTIAL_KERNEL_SOURCES = ("gqa_api.hip", "gqa_internal.h", "gqa_mfma_tile.h", "gqa_partial_mfma.hip")
@@ -32,8 +39,11 @@ PARTIAL_KERNEL_SOURCES = ("gqa_api.hip", "gqa_internal.h", "gqa_mfma_tile.h", "g
 def measured_traffic(config_index: int):
     """HBM bytes per launch of the partial kernel from the committed counter summary, or None when
     the sources the kernel is built from (its own file, the tile primitives, the shared declarations
-    and the launch code) have changed since the counters were taken."""
+    and the launch code) have changed since the counters were taken, when the in-tree library is
+    older than those sources, or when GQA_DECODE_LIBRARY selects another build."""
     import hashlib
+    if os.environ.get("GQA_DECODE_LIBRARY"):
+        return None                 # another build of the library is loaded: the committed counters are not its
     path = os.path.join(ROOT, "profiles", "partial_mfma_kernel_hbm_traffic.txt")
     if not os.path.exists(path):
         return None
@@ -47,6 +57,10 @@ def measured_traffic(config_index: int):
         h.update(name.encode())
         h.update(open(os.path.join(ROOT, "paper_2510_07356_amd", "csrc", name), "rb").read())
     if kv.get("source_sha256") != h.hexdigest():
+        return None
+    lib = os.path.join(ROOT, "paper_2510_07356_amd", "libgqa_decode.so")
+    newest = max(os.path.getmtime(os.path.join(ROOT, "paper_2510_07356_amd", "csrc", n)) for n in PARTIAL_KERNEL_SOURCES)
+    if not os.path.exists(lib) or os.path.getmtime(lib) < newest:
         return None
     v = kv.get(f"config{config_index}_partial_traffic_bytes")
     return int(v) if v is not None else None
@@ -105,6 +119,16 @@ def bench_shared_prefix(args) -> int:
         "speedup_vs_unshared": round(ms_plain / ms, 4),
         "max_abs_diff_vs_unshared": float((out - out2).abs().max()),
     }
+    if not args.no_cpu_baseline:
+        import numpy as np
+        from oracle import shared_prefix_attn
+        t0 = time.perf_counter()
+        ref = shared_prefix_attn(w.q, sw.kp, sw.vp, sw.prefix_lens, sw.group_start, w.k, w.v, w.kv_lens, w.scale)
+        err = out.double().cpu().numpy() - ref.out
+        result["parity"] = {"max_abs": float(np.abs(err).max()),
+                            "rel_l2": float(np.linalg.norm(err) / np.linalg.norm(ref.out)),
+                            "lse_max_abs": float(np.abs(lse.double().cpu().numpy() - ref.lse).max()),
+                            "oracle_seconds": round(time.perf_counter() - t0, 3)}
     print(json.dumps(result), flush=True)
     return 0
 
@@ -244,17 +268,162 @@ def bench_decode_step(args) -> int:
     return 0
 
 
+def run_decode_config(index, steps, warmup, args, with_cpu=True, with_stream_read=False, events_every=EVENT_STRIDE):
+    """Times gqa_decode_attn on one named configuration.  Returns (summary dict, details dict): the
+    summary is the per-configuration entry of the JSON line, the details feed the headline keys."""
+    import numpy as np
+    import torch
+    from paper_2510_07356_amd import binding, workloads
+    w = workloads.make_config(index, layout=args.layout)
+    # rotate over enough copies of the cache that repeated calls cannot be served from the 256 MB
+    # last-level cache or from L2: copies x K/V bytes >= 1 GiB
+    copies = args.copies if args.copies > 0 else max(2, -(-(1 << 30) // max(w.kv_bytes, 1)))
+    copies = min(copies, 1024)
+    devs = [binding.to_device(w) for _ in range(copies)]
+    params = binding.make_params(devs[0]["q"], devs[0]["k"], devs[0]["v"], w.max_kv_len, w.scale,
+                                 w.page_size, devs[0]["block_table"], args.chunk, args.variant)
+    host_lens = None if args.no_host_lens else w.kv_lens
+    plan = binding.gqa_decode_plan_info(params, host_lens)
+    ws = torch.empty(binding.gqa_decode_workspace_bytes(params), dtype=torch.uint8, device="cuda:0")
+    out = torch.empty((w.batch, w.num_q_heads, w.head_dim), dtype=torch.float32, device="cuda:0")
+    lse = torch.empty((w.batch, w.num_q_heads), dtype=torch.float32, device="cuda:0")
+    calls = [binding.Call(params, d["q"], d["k"], d["v"], d["kv_lens"], d["block_table"], host_lens,
+                          out, lse, ws) for d in devs]
+    timer = binding.Timer(steps)
+
+    for i in range(warmup):
+        calls[i % copies]()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        # every events_every-th step carries the event records around its kernels
+        calls[i % copies](timer if i % events_every == 0 else None)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    partial_calls, combine_calls = timer.read_calls(steps)
+    timer.close()
+    n_timed = len(partial_calls)
+    assert n_timed == (steps + events_every - 1) // events_every
+    ms_per_step = (t1 - t0) * 1e3 / steps
+    partial_avg_ms, combine_avg_ms = sum(partial_calls) / n_timed, sum(combine_calls) / n_timed
+
+    kv_bytes = w.kv_bytes
+    value = kv_bytes / (ms_per_step * 1e-3) / 1e12
+    achieved = kv_bytes / (partial_avg_ms * 1e-3) / 1e9
+    summary = {
+        "config": index, "name": w.name, "kv_bytes": kv_bytes, "steps": steps, "warmup": warmup,
+        "ms_per_step": round(ms_per_step, 5), "TBps": round(value, 4),
+        "pct_of_hbm_peak": round(100.0 * value * 1e3 / HBM_PEAK_GBPS, 2),
+        "sequences_per_s": round(w.batch / (ms_per_step * 1e-3), 1),
+        "partial_kernel_us": round(partial_avg_ms * 1e3, 2), "combine_kernel_us": round(combine_avg_ms * 1e3, 2),
+        "partial_kernel_frac_of_hbm_peak": round(achieved / HBM_PEAK_GBPS, 4),
+        "cache_copies_rotated": copies,
+    }
+    if copies * kv_bytes < (1 << 30):
+        summary["note"] = "copies x K/V bytes < 1 GiB: may be served from the last-level cache, not an HBM figure"
+    elif kv_bytes < (64 << 20):
+        summary["note"] = "launch-bound: the call is a few microseconds of traffic"
+    details = {"w": w, "plan": plan, "copies": copies, "ms_per_step": ms_per_step, "value": value,
+               "partial_calls": partial_calls, "partial_avg_ms": partial_avg_ms, "combine_avg_ms": combine_avg_ms,
+               "n_timed": n_timed, "achieved": achieved}
+
+    if with_stream_read:
+        kflat = devs[0]["k"].untyped_storage()
+        src = torch.empty(0, dtype=torch.uint8, device="cuda:0").set_(kflat)
+        sink = torch.empty(1 << 16, dtype=torch.int32, device="cuda:0")
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        best = float("inf")
+        for _ in range(5):
+            ev0.record()
+            binding.gqa_decode_stream_read(src, sink, 8192)
+            ev1.record()
+            ev1.synchronize()
+            best = min(best, ev0.elapsed_time(ev1))
+        details["stream_read_GBps"] = src.numel() / best / 1e6
+
+    if with_cpu:
+        from oracle import decode_attn
+        reps, t_cpu_total = 0, 0.0
+        while t_cpu_total < args.cpu_seconds and reps < 50:     # bounded wall time on all host cores
+            t3 = time.perf_counter()
+            ref = decode_attn(w.q, w.k, w.v, w.kv_lens, w.scale, block_table=w.block_table, page_size=w.page_size)
+            t_cpu_total += time.perf_counter() - t3
+            reps += 1
+        t_cpu = t_cpu_total / reps
+        out.fill_(float("nan"))
+        lse.fill_(float("nan"))
+        calls[0]()
+        torch.cuda.synchronize()
+        got = out.double().cpu().numpy()
+        err = got - ref.out
+        live = w.kv_lens > 0
+        summary["parity"] = {"max_abs": float(np.abs(err).max()),
+                             "rel_l2": float(np.linalg.norm(err) / np.linalg.norm(ref.out)),
+                             "lse_max_abs": float(np.abs(lse.double().cpu().numpy()[live] - ref.lse[live]).max()),
+                             "finite": bool(np.isfinite(got).all())}
+        summary["oracle_seconds"] = round(t_cpu, 4)
+        summary["oracle_threads"] = ref.threads
+        details.update(ref_threads=ref.threads, t_cpu=t_cpu, reps=reps)
+    del calls, devs, ws
+    torch.cuda.empty_cache()
+    return summary, details
+
+
+def prefill_block(args):
+    """Causal prefill at 32,768 tokens and on a ragged batch of 64 prompts: TFLOP/s against the bf16 matrix peak."""
+    import io
+    import contextlib
+    blocks = {}
+    for key, extra in (("causal_32768", dict(seq_len=32768, prompts=0, steps=5, warmup=2)),
+                       ("ragged_64_prompts", dict(seq_len=0, prompts=64, steps=10, warmup=2))):
+        sub = argparse.Namespace(**{**vars(args), **extra})
+        buf = io.StringIO()
+        with contextlib.redirect_stdout(buf):
+            bench_prefill(sub)
+        d = json.loads(buf.getvalue().strip().splitlines()[-1])
+        blocks[key] = {"workload": d["config"]["workload"], "steps": d["steps"], "ms_per_step": d["ms_per_step"],
+                       "TFLOPps": d["value"], "frac_of_mfma_peak": d["roofline"]["frac"],
+                       "tokens_per_s": d["tokens_per_s"]}
+    return blocks
+
+
+def shared_prefix_block(args):
+    """Shared-prefix decode on the two sampling batches of the paper (5 and 10 samples per prompt)."""
+    import io
+    import contextlib
+    blocks = {}
+    for key, extra in (("12_prompts_x_5_samples", dict(tasks=12, samples=5, steps=100, warmup=10)),
+                       ("6_prompts_x_10_samples", dict(tasks=6, samples=10, steps=100, warmup=10))):
+        sub = argparse.Namespace(**{**vars(args), **extra})
+        buf = io.StringIO()
+        with contextlib.redirect_stdout(buf):
+            bench_shared_prefix(sub)
+        d = json.loads(buf.getvalue().strip().splitlines()[-1])
+        blocks[key] = {"workload": d["config"]["workload"], "steps": d["steps"], "ms_per_step": d["ms_per_step"],
+                       "physical_kv_bytes": d["config"]["physical_kv_bytes"],
+                       "logical_kv_bytes": d["config"]["logical_kv_bytes"],
+                       "physical_TBps": d["physical_TBps"], "frac_of_hbm_peak_physical": round(d["pct_of_hbm_peak_physical"] / 100, 4),
+                       "unshared_ms_per_step": d["unshared_ms_per_step"], "speedup_vs_unshared": d["speedup_vs_unshared"],
+                       "parity": d.get("parity")}
+    return blocks
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=2, help="index into the five named configurations")
+    ap.add_argument("--config", type=int, default=None,
+                    help="index into the five named configurations: time only that one (default: the ragged "
+                         "16K batch as the headline, then every configuration, prefill and shared prefix)")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="headline configuration only: no per-configuration, prefill and shared-prefix blocks")
     ap.add_argument("--chunk", type=int, default=0, help="KV tokens per share (0 = one share per workgroup)")
     ap.add_argument("--variant", type=int, default=0, help="0 = matrix-core kernel, 1 = vector-ALU kernel")
     ap.add_argument("--layout", default="head_major")
     ap.add_argument("--no-host-lens", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=1.5, help="wall time the oracle is repeated for, per configuration")
     ap.add_argument("--calibration-copy", type=int, default=0, metavar="MIB",
                     help="also run the plain copy kernel over this many MiB, three times (counter scaling in profiles)")
     ap.add_argument("--no-stream-read", action="store_true", help="skip the streaming-read probe over one cache copy")
@@ -277,7 +446,7 @@ def main() -> int:
 
     import numpy as np
     import torch
-    from paper_2510_07356_amd import binding, workloads
+    from paper_2510_07356_amd import binding
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -289,50 +458,13 @@ def main() -> int:
     if args.decode_step:
         return bench_decode_step(args)
     torch.cuda.set_device(0)
-    t_gen = time.time()
-    w = workloads.make_config(args.config, layout=args.layout)
-    t_gen = time.time() - t_gen
-    copies = args.copies if args.copies > 0 else max(2, -(-(1 << 30) // max(w.kv_bytes, 1)))
-    copies = min(copies, 64)
-    devs = [binding.to_device(w) for _ in range(copies)]
-    params = binding.make_params(devs[0]["q"], devs[0]["k"], devs[0]["v"], w.max_kv_len, w.scale,
-                                 w.page_size, devs[0]["block_table"], args.chunk, args.variant)
-    host_lens = None if args.no_host_lens else w.kv_lens
-    plan = binding.gqa_decode_plan_info(params, host_lens)
-    ws = torch.empty(binding.gqa_decode_workspace_bytes(params), dtype=torch.uint8, device="cuda:0")
-    out = torch.empty((w.batch, w.num_q_heads, w.head_dim), dtype=torch.float32, device="cuda:0")
-    lse = torch.empty((w.batch, w.num_q_heads), dtype=torch.float32, device="cuda:0")
-    calls = [binding.Call(params, d["q"], d["k"], d["v"], d["kv_lens"], d["block_table"], host_lens,
-                          out, lse, ws) for d in devs]
-    timer = binding.Timer(args.steps)
-
-    for i in range(args.warmup):
-        calls[i % copies]()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        # every EVENT_STRIDE-th step carries the event records around its kernels
-        calls[i % copies](timer if i % EVENT_STRIDE == 0 else None)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    partial_calls, combine_calls = timer.read_calls(args.steps)
-    n_timed = len(partial_calls)
-    assert n_timed == (args.steps + EVENT_STRIDE - 1) // EVENT_STRIDE
-    partial_ms, combine_ms = sum(partial_calls), sum(combine_calls)
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-
-    # the same loop without the event records, for the record only
-    torch.cuda.synchronize()
-    t2 = time.perf_counter()
-    for i in range(args.steps):
-        calls[i % copies]()
-    torch.cuda.synchronize()
-    ms_plain = (time.perf_counter() - t2) * 1e3 / args.steps
-
-    kv_bytes = w.kv_bytes
-    value = kv_bytes / (ms_per_step * 1e-3) / 1e12
-    partial_avg_ms = partial_ms / n_timed
-    achieved = kv_bytes / (partial_avg_ms * 1e-3) / 1e9
+    binding.gqa_decode_init()
+    headline = HEADLINE_CONFIG if args.config is None else args.config
+    extras = args.config is None and not args.no_extras
+    summary, d = run_decode_config(headline, args.steps, args.warmup, args, with_cpu=not args.no_cpu_baseline,
+                                   with_stream_read=not args.no_stream_read)
+    w, plan = d["w"], d["plan"]
+    kv_bytes, value, ms_per_step = w.kv_bytes, d["value"], d["ms_per_step"]
 
     result = {
         "metric": "decode_attn_kv_read_throughput",
@@ -348,14 +480,14 @@ def main() -> int:
         "dtype": "bf16",
         "data": "synthetic",
         "config": {
-            "workload": f"{w.name} (configs[{args.config}]): B={w.batch} Hq={w.num_q_heads} Hkv={w.num_kv_heads} "
+            "workload": f"{w.name} (configs[{headline}]): B={w.batch} Hq={w.num_q_heads} Hkv={w.num_kv_heads} "
                         f"D={w.head_dim} kv_tokens={w.kv_tokens} {'paged' if w.page_size else 'contiguous'} "
                         f"{w.layout} bf16 cache",
             "kv_bytes_per_step": kv_bytes,
             "share_tokens": plan.share_tokens,
             "workgroups": plan.workgroups,
             "kernel_variant": args.variant,
-            "cache_copies_rotated": copies,
+            "cache_copies_rotated": d["copies"],
         },
         "pct_of_hbm_peak": round(100.0 * value * 1e3 / HBM_PEAK_GBPS, 2),
         # everything a call moves: K/V once, Q, the output, and the partial results written by the partial
@@ -366,19 +498,19 @@ def main() -> int:
         "sequences_per_s": round(w.batch / (ms_per_step * 1e-3), 1),
         # derived: attention-only bound on generated tokens/s if a 64-layer model made this call per layer
         "derived_tokens_per_s_64_layers": round(w.batch / (64 * ms_per_step * 1e-3), 1),
-        "ms_per_step_without_event_records": round(ms_plain, 5),
-        "kernel_ms": {"partial": round(partial_avg_ms, 5), "partial_median": round(float(np.median(partial_calls)), 5),
-                      "partial_min": round(min(partial_calls), 5),
-                      "combine": round(combine_ms / n_timed, 5), "launches_timed": n_timed},
+        "kernel_ms": {"partial": round(d["partial_avg_ms"], 5),
+                      "partial_median": round(float(np.median(d["partial_calls"])), 5),
+                      "partial_min": round(min(d["partial_calls"]), 5),
+                      "combine": round(d["combine_avg_ms"], 5), "launches_timed": d["n_timed"]},
         "roofline": {
             "kernel": "partial_mfma_kernel" if args.variant == 0 else "partial_valu_kernel",
             "bound": "hbm",
-            "achieved": round(achieved, 1),
+            "achieved": round(d["achieved"], 1),
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
-            "frac": round(achieved / HBM_PEAK_GBPS, 4),
-            "traffic": measured_traffic(args.config) if (args.variant == 0 and args.chunk == 0
-                                                         and args.layout == "head_major") else None,
+            "frac": round(d["achieved"] / HBM_PEAK_GBPS, 4),
+            "traffic": measured_traffic(headline) if (args.variant == 0 and args.chunk == 0
+                                                     and args.layout == "head_major") else None,
         },
     }
 
@@ -391,48 +523,38 @@ def main() -> int:
         torch.cuda.synchronize()
         result["calibration_copy_bytes"] = n
         del src, dst
-    if not args.no_stream_read:
-        kflat = devs[0]["k"].untyped_storage()
-        src = torch.empty(0, dtype=torch.uint8, device="cuda:0").set_(kflat)
-        sink = torch.empty(1 << 16, dtype=torch.int32, device="cuda:0")
-        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        best = float("inf")
-        for _ in range(5):
-            ev0.record()
-            binding.gqa_decode_stream_read(src, sink, 8192)
-            ev1.record()
-            ev1.synchronize()
-            best = min(best, ev0.elapsed_time(ev1))
-        ceiling = src.numel() / best / 1e6
-        result["stream_read_probe_GBps"] = round(ceiling, 1)
-        result["pct_of_stream_read_probe"] = round(100.0 * value * 1e3 / ceiling, 2)
+    if "stream_read_GBps" in d:
+        result["stream_read_probe_GBps"] = round(d["stream_read_GBps"], 1)
+        result["pct_of_stream_read_probe"] = round(100.0 * value * 1e3 / d["stream_read_GBps"], 2)
 
     if not args.no_cpu_baseline:
         from oracle import decode_attn
-        reps, t_cpu_total = 0, 0.0
-        while t_cpu_total < 1.5 and reps < 50:        # bounded: a few seconds of wall time on all host cores
-            t3 = time.perf_counter()
-            ref = decode_attn(w.q, w.k, w.v, w.kv_lens, w.scale, block_table=w.block_table, page_size=w.page_size)
-            t_cpu_total += time.perf_counter() - t3
-            reps += 1
-        t_cpu = t_cpu_total / reps
         t4 = time.perf_counter()
         decode_attn(w.q, w.k, w.v, w.kv_lens, w.scale, block_table=w.block_table, page_size=w.page_size, threads=1)
         t_one = time.perf_counter() - t4
-        calls[0]()
-        torch.cuda.synchronize()
-        err = out.double().cpu().numpy() - ref.out
         result["cpu_baseline"] = {
-            "value": round(kv_bytes / t_cpu / 1e12, 6),
+            "value": round(kv_bytes / d["t_cpu"] / 1e12, 6),
             "unit": "TB/s",
-            "cores": ref.threads,
+            "cores": d["ref_threads"],
             "kind": "oracle",
-            "sample": f"the whole workload ({w.batch} sequences, {w.kv_tokens} KV tokens), mean of {reps} runs, "
-                      f"{t_cpu:.3f} s wall each on {ref.threads} threads; one run on a single thread: {t_one:.2f} s",
+            "sample": f"the whole workload ({w.batch} sequences, {w.kv_tokens} KV tokens), mean of {d['reps']} runs, "
+                      f"{d['t_cpu']:.3f} s wall each on {d['ref_threads']} threads; one run on a single thread: {t_one:.2f} s",
             "single_thread_value": round(kv_bytes / t_one / 1e12, 6),
         }
-        result["parity"] = {"max_abs": float(np.abs(err).max()),
-                            "rel_l2": float(np.linalg.norm(err) / np.linalg.norm(ref.out))}
+        result["parity"] = summary["parity"]
+
+    if extras:
+        # every named configuration with its own step count (the headline keys above keep --steps / --warmup),
+        # then the two neighbouring workloads; all inside this one run so that one clock covers them
+        del w, d
+        per_config = []
+        for i in range(5):
+            inner_steps = 400 if i == 0 else 200
+            s_i, _ = run_decode_config(i, inner_steps, 20, args, with_cpu=not args.no_cpu_baseline, events_every=2)
+            per_config.append(s_i)
+        result["per_config"] = per_config
+        result["prefill"] = prefill_block(args)
+        result["shared_prefix"] = shared_prefix_block(args)
     print(json.dumps(result), flush=True)
     return 0
 
