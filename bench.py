@@ -181,6 +181,50 @@ def bench_prefill(args) -> int:
     return 0
 
 
+PROBE_MODES = {0: "non-temporal, 1 KB per load instruction (V path), 1 tile in flight",
+               1: "non-temporal, operand-shaped 16 rows x 64 B (K path), 1 tile in flight",
+               2: "non-temporal, 1 KB per load, then through LDS (ds_write_b128 + operand-shaped ds_read_b128)",
+               3: "ordinary loads, operand-shaped, 1 tile in flight",
+               4: "non-temporal, operand-shaped, 2 tiles in flight",
+               5: "non-temporal, 1 KB per load, 2 tiles in flight",
+               6: "non-temporal, the kernel's mix: half operand-shaped (K), half 1 KB per load (V), 1 tile in flight",
+               7: "ordinary loads, the kernel's mix, 1 tile in flight"}
+
+
+def bench_probe(args) -> int:
+    """Access-pattern probe (gqa_decode_stream_probe) over a buffer of the headline batch's K/V size:
+    every mode at one wavefront per SIMD, then the kernel's own mix at 1 to 16 wavefronts per CU."""
+    import torch
+    from paper_2510_07356_amd import binding
+    torch.cuda.set_device(0)
+    nbytes = 2_408_591_360 // 16384 * 16384
+    bufs = [torch.full((nbytes,), 1, dtype=torch.uint8, device="cuda:0") for _ in range(2)]
+    sink = torch.empty(4 * 4096, dtype=torch.int32, device="cuda:0")
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed(workgroups, mode):
+        ts = []
+        for i in range(args.warmup + args.steps):
+            ev0.record()
+            binding.gqa_decode_stream_probe(bufs[i % 2], sink, workgroups, mode)
+            ev1.record()
+            ev1.synchronize()
+            if i >= args.warmup:
+                ts.append(ev0.elapsed_time(ev1))
+        ts.sort()
+        return {"best_us": round(ts[0] * 1e3, 1), "median_us": round(ts[len(ts) // 2] * 1e3, 1),
+                "median_GBps": round(nbytes / ts[len(ts) // 2] / 1e6, 1)}
+
+    rows = []
+    for mode in sorted(PROBE_MODES):
+        rows.append({"mode": mode, "what": PROBE_MODES[mode], "workgroups": 256, "wavefronts_per_cu": 4, **timed(256, mode)})
+    for wgs in (64, 128, 512, 768, 1024):
+        rows.append({"mode": 6, "what": PROBE_MODES[6], "workgroups": wgs, "wavefronts_per_cu": wgs // 64, **timed(wgs, 6)})
+    print(json.dumps({"metric": "stream_probe_read_throughput", "unit": "GB/s", "bytes_per_launch": nbytes,
+                      "steps": args.steps, "warmup": args.warmup, "rows": rows}), flush=True)
+    return 0
+
+
 def bench_decode_step(args) -> int:
     """One decode step of an L-layer model on the ragged 64-sequence batch with a paged cache: per
     layer the new token's K/V are appended (rotary included) and attention runs over that layer's
@@ -275,6 +319,11 @@ def run_decode_config(index, steps, warmup, args, with_cpu=True, with_stream_rea
     import torch
     from paper_2510_07356_amd import binding, workloads
     w = workloads.make_config(index, layout=args.layout)
+    if args.page_size > 0 and w.page_size == 0:
+        # the same lengths and shape as a paged cache with a randomly permuted pool (what paging costs)
+        width = -(-int(w.k.shape[2]) // args.page_size)
+        w = workloads.make_paged(f"{w.name}_paged{args.page_size}", index, w.batch, w.num_q_heads, w.num_kv_heads,
+                                 w.kv_lens, table_width=width, page_size=args.page_size, layout=args.layout)
     # rotate over enough copies of the cache that repeated calls cannot be served from the 256 MB
     # last-level cache or from L2: copies x K/V bytes >= 1 GiB
     copies = args.copies if args.copies > 0 else max(2, -(-(1 << 30) // max(w.kv_bytes, 1)))
@@ -421,6 +470,8 @@ def main() -> int:
     ap.add_argument("--chunk", type=int, default=0, help="KV tokens per share (0 = one share per workgroup)")
     ap.add_argument("--variant", type=int, default=0, help="0 = matrix-core kernel, 1 = vector-ALU kernel")
     ap.add_argument("--layout", default="head_major")
+    ap.add_argument("--page-size", type=int, default=0,
+                    help="run a contiguous configuration's lengths on a paged cache with this page size instead")
     ap.add_argument("--no-host-lens", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=1.5, help="wall time the oracle is repeated for, per configuration")
@@ -435,6 +486,8 @@ def main() -> int:
     ap.add_argument("--decode-step", action="store_true",
                     help="benchmark one graph-captured decode step of --layers layers (append + attention per layer)")
     ap.add_argument("--layers", type=int, default=64)
+    ap.add_argument("--probe", action="store_true",
+                    help="time the access-pattern probe (the evidence behind the partial kernel's load path) instead")
     ap.add_argument("--tasks", type=int, default=12)
     ap.add_argument("--samples", type=int, default=5)
     ap.add_argument("--copies", type=int, default=0, help="cache copies to rotate over (0 = enough for 1 GiB)")
@@ -457,6 +510,8 @@ def main() -> int:
         return bench_prefill(args)
     if args.decode_step:
         return bench_decode_step(args)
+    if args.probe:
+        return bench_probe(args)
     torch.cuda.set_device(0)
     binding.gqa_decode_init()
     headline = HEADLINE_CONFIG if args.config is None else args.config
@@ -509,7 +564,7 @@ def main() -> int:
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": round(d["achieved"] / HBM_PEAK_GBPS, 4),
-            "traffic": measured_traffic(headline) if (args.variant == 0 and args.chunk == 0
+            "traffic": measured_traffic(headline) if (args.variant == 0 and args.chunk == 0 and args.page_size == 0
                                                      and args.layout == "head_major") else None,
         },
     }

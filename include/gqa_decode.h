@@ -362,6 +362,21 @@ int gqa_decode_kv_append(const gqa_append_params* params,
 int gqa_decode_stream_read(const void* src, size_t bytes, void* sink, int32_t workgroups, void* stream);
 
 /*
+ * Access-pattern probe behind the design choices of the split-KV kernel: persistent
+ * wavefronts (4 per workgroup, `workgroups` <= 4096 of them) stream floor(bytes / 16384)
+ * tiles of 16 KB from `src`, each wavefront an equal contiguous run, folding the data
+ * into one word per wavefront in `sink` (at least 16 * workgroups bytes).  mode:
+ *   0  non-temporal loads, 1 KB contiguous per load instruction (how V is read), one tile in flight
+ *   1  non-temporal, matrix-operand-shaped: 16 rows x 64 bytes per load instruction (how K is read)
+ *   2  as 0, then through LDS (ds_write_b128, operand-shaped ds_read_b128): an LDS-staged tile
+ *   3  as 1 with ordinary (temporal) loads
+ *   4  as 1 with two tiles in flight per wavefront (double-buffered)
+ *   5  as 0 with two tiles in flight
+ * Not part of the attention path; the benchmark's --probe mode times it.
+ */
+int gqa_decode_stream_probe(const void* src, size_t bytes, void* sink, int32_t workgroups, int32_t mode, void* stream);
+
+/*
  * Plain device-to-device copy of `bytes` (a multiple of 16; src and dst
  * 16-byte aligned, not overlapping) by a grid-stride kernel.  It reads and
  * writes exactly `bytes` each, which makes it the known-size reference that

@@ -30,7 +30,7 @@ EXPORTS = ("gqa_decode_version", "gqa_decode_strerror", "gqa_decode_init", "gqa_
            "gqa_decode_static_scratch_bytes", "gqa_decode_attn_static",
            "gqa_prefill_attn", "gqa_prefill_attn_varlen", "gqa_decode_kv_append",
            "gqa_cascade_workspace_bytes", "gqa_decode_attn_shared_prefix",
-           "gqa_decode_stream_read", "gqa_decode_stream_copy",
+           "gqa_decode_stream_read", "gqa_decode_stream_copy", "gqa_decode_stream_probe",
            "gqa_timer_create", "gqa_timer_destroy", "gqa_timer_read", "gqa_timer_read_calls")
 
 
@@ -133,6 +133,8 @@ def _load() -> ctypes.CDLL:
     lib.gqa_decode_kv_append.argtypes = [ctypes.POINTER(gqa_append_params)] + [vp] * 10
     lib.gqa_decode_stream_read.restype = ctypes.c_int
     lib.gqa_decode_stream_read.argtypes = [vp, ctypes.c_size_t, vp, ctypes.c_int32, vp]
+    lib.gqa_decode_stream_probe.restype = ctypes.c_int
+    lib.gqa_decode_stream_probe.argtypes = [vp, ctypes.c_size_t, vp, ctypes.c_int32, ctypes.c_int32, vp]
     lib.gqa_decode_stream_copy.restype = ctypes.c_int
     lib.gqa_decode_stream_copy.argtypes = [vp, vp, ctypes.c_size_t, ctypes.c_int32, vp]
     return lib
@@ -476,6 +478,17 @@ def gqa_decode_stream_read(src: torch.Tensor, sink: torch.Tensor, workgroups: in
     if sink.numel() * sink.element_size() < 4 * workgroups:
         raise ValueError("sink too small")
     rc = _lib.gqa_decode_stream_read(src.data_ptr(), nbytes, sink.data_ptr(), int(workgroups), s.cuda_stream)
+    if rc != GQA_OK:
+        raise GqaError(rc)
+
+
+def gqa_decode_stream_probe(src: torch.Tensor, sink: torch.Tensor, workgroups: int, mode: int,
+                            stream: Optional[torch.cuda.Stream] = None) -> None:
+    s = stream if stream is not None else torch.cuda.current_stream(src.device)
+    if sink.numel() * sink.element_size() < 16 * workgroups:
+        raise ValueError("sink too small")
+    rc = _lib.gqa_decode_stream_probe(src.data_ptr(), src.numel() * src.element_size(), sink.data_ptr(),
+                                      int(workgroups), int(mode), s.cuda_stream)
     if rc != GQA_OK:
         raise GqaError(rc)
 

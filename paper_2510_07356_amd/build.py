@@ -38,4 +38,10 @@ def build_library(verbose: bool = False, out: str = LIB, defines=()) -> str:
 
 
 if __name__ == "__main__":
-    print(build_library(verbose=True))
+    import argparse
+    ap = argparse.ArgumentParser(description="build libgqa_decode.so (default: in-tree, default tunables)")
+    ap.add_argument("--out", default=LIB, help="output path; load it with GQA_DECODE_LIBRARY=<path>")
+    ap.add_argument("-D", dest="defines", action="append", default=[],
+                    help="compile-time tunable, e.g. -D GQA_MFMA_WGS_PER_CU=2 (see the #ifndef blocks in csrc/)")
+    a = ap.parse_args()
+    print(build_library(verbose=True, out=a.out, defines=a.defines))

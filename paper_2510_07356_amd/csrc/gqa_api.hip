@@ -576,6 +576,14 @@ int gqa_decode_stream_read(const void* src, size_t bytes, void* sink, int32_t wo
                ? GQA_OK : GQA_ERR_LAUNCH;
 }
 
+int gqa_decode_stream_probe(const void* src, size_t bytes, void* sink, int32_t workgroups, int32_t mode, void* stream) {
+    if (!src || !sink || workgroups < 1 || workgroups > 4096 || bytes < 16384 || bytes / 16384 > 0x7fffffffULL ||
+        !aligned16(src) || mode < 0 || mode > 7)
+        return GQA_ERR_INVALID_ARG;
+    return gqa::launch_stream_probe(src, bytes, sink, workgroups, mode, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? GQA_OK : GQA_ERR_LAUNCH;
+}
+
 int gqa_decode_stream_copy(const void* src, void* dst, size_t bytes, int32_t workgroups, void* stream) {
     if (!src || !dst || workgroups < 1 || bytes % 16 != 0 || !aligned16(src) || !aligned16(dst))
         return GQA_ERR_INVALID_ARG;

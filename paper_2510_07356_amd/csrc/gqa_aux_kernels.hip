@@ -107,6 +107,124 @@ hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, int wor
 }
 
 // ---------------------------------------------------------------------------
+// Access-pattern probe: persistent wavefronts stream 16 KB tiles (the K or V part of one 32-token
+// tile of the attention kernel: 64 rows of 256 bytes) the way a design candidate of the partial
+// kernel would, with the arithmetic replaced by an xor fold.  It prices the choices of the
+// partial kernel in achieved HBM bandwidth:
+//   PATTERN 0  row-coalesced: one load instruction = 4 whole rows, 1 KB contiguous (the V path)
+//   PATTERN 1  matrix-operand-shaped: lane (i, kb) reads 16 bytes of row 16 hf + i at byte
+//              64 j + 16 kb, so a load instruction covers 16 rows x 64 bytes (the K path)
+//   PATTERN 2  row-coalesced, then through LDS: written with ds_write_b128, read back in the
+//              operand shape (what staging K in LDS would add)
+//   NT         non-temporal loads or ordinary ones
+//   TILES      tiles in flight per wavefront: 1 (registers refilled as soon as they are consumed)
+//              or 2 (double-buffered)
+// Every wavefront owns an equal, contiguous run of tiles, as in the stream split.
+// ---------------------------------------------------------------------------
+template <bool NT>
+__device__ __forceinline__ u32x4 probe_load(const u32x4* p) {
+    if (NT) return __builtin_nontemporal_load(p);
+    return *p;
+}
+
+template <int PATTERN, bool NT>
+__device__ __forceinline__ void probe_request(const u32x4* tile, int lane, u32x4 (&r)[16]) {
+    if (PATTERN == 1) {
+        const int i = lane & 15, kb = lane >> 4;
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                r[4 * hf + j] = probe_load<NT>(tile + (16 * hf + i) * 16 + 4 * j + kb);            // rows 0..31
+                r[8 + 4 * hf + j] = probe_load<NT>(tile + 512 + (16 * hf + i) * 16 + 4 * j + kb);  // rows 32..63
+            }
+    } else if (PATTERN == 3) {
+        // the attention kernel's own mix: rows 0..31 operand-shaped (K), rows 32..63 row-coalesced (V)
+        const int i = lane & 15, kb = lane >> 4;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) r[8 + j] = probe_load<NT>(tile + 512 + 64 * j + lane);
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) r[4 * hf + j] = probe_load<NT>(tile + (16 * hf + i) * 16 + 4 * j + kb);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) r[j] = probe_load<NT>(tile + 64 * j + lane);
+    }
+}
+
+template <int PATTERN>
+__device__ __forceinline__ u32x4 probe_consume(u32x4 (&r)[16], u32x4* lds_wave, int lane) {
+    u32x4 acc = {0, 0, 0, 0};
+    if (PATTERN == 2) {
+        // one 16 KB tile through this wavefront's own LDS region: 1 KB per store instruction in, operand-shaped out
+        const int i = lane & 15, kb = lane >> 4;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) lds_wave[64 * j + lane] = r[j];
+#pragma unroll
+        for (int hf = 0; hf < 4; ++hf)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc ^= lds_wave[(16 * hf + i) * 16 + 4 * j + kb];
+    } else {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc ^= r[j];
+    }
+    return acc;
+}
+
+template <int PATTERN, bool NT, int TILES>
+__global__ __launch_bounds__(256, 1) void stream_probe_kernel(const u32x4* __restrict__ src, int n_tiles,
+                                                              uint32_t* __restrict__ sink) {
+    extern __shared__ u32x4 probe_lds[];                 // PATTERN 2: 16 KB per wavefront
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int worker = blockIdx.x * 4 + wave, workers = gridDim.x * 4;
+    const int share = (n_tiles + workers - 1) / workers;
+    const int first = min(worker * share, n_tiles), last = min(first + share, n_tiles);
+    u32x4* lds_wave = probe_lds + (PATTERN == 2 ? wave * 1024 : 0);
+    u32x4 acc = {0, 0, 0, 0};
+    u32x4 ra[16], rb[16];
+    if (first < last) {
+        probe_request<PATTERN, NT>(src + (size_t)first * 1024, lane, ra);
+        if (TILES == 2) probe_request<PATTERN, NT>(src + (size_t)min(first + 1, last - 1) * 1024, lane, rb);
+        for (int t = first; t < last; t += TILES) {
+            // the refill is unconditional (the last tiles are requested again) so that the number of
+            // loads in flight is the same on every iteration
+            acc ^= probe_consume<PATTERN>(ra, lds_wave, lane);
+            probe_request<PATTERN, NT>(src + (size_t)min(t + TILES, last - 1) * 1024, lane, ra);
+            if (TILES == 2) {
+                if (t + 1 < last) acc ^= probe_consume<PATTERN>(rb, lds_wave, lane);
+                probe_request<PATTERN, NT>(src + (size_t)min(t + 3, last - 1) * 1024, lane, rb);
+            }
+        }
+        // drain what is still in flight
+        acc ^= probe_consume<PATTERN>(ra, lds_wave, lane);
+        if (TILES == 2) acc ^= probe_consume<PATTERN>(rb, lds_wave, lane);
+    }
+    uint32_t x = acc.x ^ acc.y ^ acc.z ^ acc.w;
+    for (int o = 32; o > 0; o >>= 1) x ^= __shfl_xor(x, o);
+    if (lane == 0) sink[worker] = x;
+}
+
+hipError_t launch_stream_probe(const void* src, size_t bytes, void* sink, int workgroups, int mode, hipStream_t s) {
+    const int n_tiles = (int)(bytes / 16384);
+    const u32x4* p = (const u32x4*)src;
+    uint32_t* k = (uint32_t*)sink;
+    const dim3 g(workgroups), b(256);
+    switch (mode) {
+        case 0: hipLaunchKernelGGL((stream_probe_kernel<0, true, 1>), g, b, 0, s, p, n_tiles, k); break;
+        case 1: hipLaunchKernelGGL((stream_probe_kernel<1, true, 1>), g, b, 0, s, p, n_tiles, k); break;
+        case 2: hipLaunchKernelGGL((stream_probe_kernel<2, true, 1>), g, b, 65536, s, p, n_tiles, k); break;
+        case 3: hipLaunchKernelGGL((stream_probe_kernel<1, false, 1>), g, b, 0, s, p, n_tiles, k); break;
+        case 4: hipLaunchKernelGGL((stream_probe_kernel<1, true, 2>), g, b, 0, s, p, n_tiles, k); break;
+        case 5: hipLaunchKernelGGL((stream_probe_kernel<0, true, 2>), g, b, 0, s, p, n_tiles, k); break;
+        case 6: hipLaunchKernelGGL((stream_probe_kernel<3, true, 1>), g, b, 0, s, p, n_tiles, k); break;
+        case 7: hipLaunchKernelGGL((stream_probe_kernel<3, false, 1>), g, b, 0, s, p, n_tiles, k); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
 // Plain copy of n16 16-byte words (grid-stride): the known-size kernel against
 // which the HBM byte counters of a profile are scaled.
 // ---------------------------------------------------------------------------

@@ -248,6 +248,7 @@ hipError_t launch_partial_mfma(const KernelArgs& a, int workgroups, hipStream_t 
 hipError_t launch_combine(const KernelArgs& a, int workgroups, hipStream_t s);
 hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, int workgroups, hipStream_t s);
 hipError_t launch_stream_copy(const void* src, void* dst, size_t bytes, int workgroups, hipStream_t s);
+hipError_t launch_stream_probe(const void* src, size_t bytes, void* sink, int workgroups, int mode, hipStream_t s);
 int partial_mfma_occupancy();   // resident workgroups per CU (from the HIP occupancy query)
 int partial_valu_occupancy();
 int partial_mfma_workers_per_group();     // independent wavefronts per workgroup of the matrix-core kernel
