@@ -228,9 +228,10 @@ int gqa_decode_attn_timed(const gqa_decode_params* params,
  * every prompt several times (5 generations per task when the data are
  * collected, Section 3.3; 10 per task at evaluation, Section 4.2), so the
  * sequences of a batch come in groups that share the prompt's keys and values.
- * Here the shared prefix of a group is stored once, and one read of it serves 16
+ * Here the shared prefix of a group is stored once, and one read of it serves 32
  * of the group's samples x heads-per-KV-head query rows (it is read
- * ceil(M * G / 16) times instead of M times); each sequence attends over
+ * ceil(M * G / 32) times instead of M times: once for 5 samples of the 40 / 8 head
+ * shape, twice for 10); each sequence attends over
  *     [ prefix of its group (prefix_lens[j] tokens) ; its own suffix (kv_lens[b] tokens) ]
  * and the result is exactly the attention defined at the top of this header
  * over that concatenation.

@@ -373,9 +373,12 @@ int gqa_timer_read_calls(gqa_timer* timer, int32_t capacity, int32_t* host_calls
 namespace {
 
 struct CascadePlan {
-    int64_t slots;
-    size_t header_bytes, prefix_bytes, ml_bytes, o_bytes;
-    size_t total_bytes() const { return header_bytes + prefix_bytes + ml_bytes + o_bytes; }
+    int64_t max_cost;        // upper bound of the stream's length on the cost axis
+    int64_t prefix_slots, suffix_slots;
+    size_t header_bytes, entry_bytes, ml_prefix_bytes, o_prefix_bytes, ml_bytes, o_bytes;
+    size_t total_bytes() const {
+        return header_bytes + entry_bytes + ml_prefix_bytes + o_prefix_bytes + ml_bytes + o_bytes;
+    }
 };
 
 int make_cascade_plan(const gqa_cascade_params* cp, CascadePlan* plan) {
@@ -386,22 +389,25 @@ int make_cascade_plan(const gqa_cascade_params* cp, CascadePlan* plan) {
     if (p->kernel_variant != 0) return GQA_ERR_UNSUPPORTED;
     if (cp->num_groups < 1 || cp->num_groups > p->batch || cp->max_prefix_len < 0) return GQA_ERR_INVALID_ARG;
     const int64_t entries = (int64_t)cp->num_groups + p->batch;
-    const int64_t max_tiles = (int64_t)p->num_kv_heads *
-        ((int64_t)cp->num_groups * gqa::tiles_of(cp->max_prefix_len) + (int64_t)p->batch * gqa::tiles_of(p->max_kv_len));
-    if (max_tiles > 0x3fffffffLL) return GQA_ERR_UNSUPPORTED;
+    plan->max_cost = (int64_t)p->num_kv_heads *
+        ((int64_t)cp->num_groups * gqa::tiles_of(cp->max_prefix_len) * 2 * gqa::kCascadeMaxTileCost +      // two reads at most
+         (int64_t)p->batch * gqa::tiles_of(p->max_kv_len) * gqa::cascade_tile_cost(1));
+    if (plan->max_cost > 0x3fffffffLL) return GQA_ERR_UNSUPPORTED;      // positions on the cost axis are int32
     int64_t shares = kMaxWorkers;
     const int fixed = p->chunk_tokens / gqa::kTileTokens;
-    if (fixed > 0 && (max_tiles + fixed - 1) / fixed > shares) shares = (max_tiles + fixed - 1) / fixed;
-    // rows: Hkv per suffix, Hkv * blocks per prefix; the blocks of all groups together are at most
-    // batch * group / 16 + num_groups
-    const int group = p->num_q_heads / p->num_kv_heads;
-    const int64_t rows = (int64_t)p->num_kv_heads *
-        ((int64_t)p->batch + ((int64_t)p->batch * group + 15) / 16 + cp->num_groups);
-    plan->slots = shares + rows;
+    if (fixed > 0) {
+        const int64_t sc = gqa::cascade_share_cost(0, fixed, 1);
+        if ((plan->max_cost + sc - 1) / sc > shares) shares = (plan->max_cost + sc - 1) / sc;
+    }
+    // a piece of a prefix row goes to slot share + 2 (group * Hkv + g) + read, a piece of a suffix row to share + b * Hkv + g
+    plan->prefix_slots = shares + 2 * (int64_t)cp->num_groups * p->num_kv_heads;
+    plan->suffix_slots = shares + (int64_t)p->batch * p->num_kv_heads;
     plan->header_bytes = 256;
-    plan->prefix_bytes = align_up(sizeof(int32_t) * 2 * ((size_t)entries + 1), 256);
-    plan->ml_bytes = align_up((size_t)plan->slots * 16 * 2 * sizeof(float), 256);
-    plan->o_bytes = align_up((size_t)plan->slots * 16 * gqa::kHeadDim * sizeof(float), 256);
+    plan->entry_bytes = align_up(sizeof(int32_t) * ((size_t)entries + 1), 256);
+    plan->ml_prefix_bytes = align_up((size_t)plan->prefix_slots * 32 * 2 * sizeof(float), 256);
+    plan->o_prefix_bytes = align_up((size_t)plan->prefix_slots * 32 * gqa::kHeadDim * sizeof(float), 256);
+    plan->ml_bytes = align_up((size_t)plan->suffix_slots * 16 * 2 * sizeof(float), 256);
+    plan->o_bytes = align_up((size_t)plan->suffix_slots * 16 * gqa::kHeadDim * sizeof(float), 256);
     return GQA_OK;
 }
 
@@ -457,8 +463,11 @@ int gqa_decode_attn_shared_prefix(const gqa_cascade_params* cp, const void* q, c
     char* ws = static_cast<char*>(workspace);
     a.header = reinterpret_cast<int32_t*>(ws);
     a.row_prefix = reinterpret_cast<int32_t*>(ws + plan.header_bytes);
-    a.part_ml = reinterpret_cast<float*>(ws + plan.header_bytes + plan.prefix_bytes);
-    a.part_o = reinterpret_cast<float*>(ws + plan.header_bytes + plan.prefix_bytes + plan.ml_bytes);
+    size_t at = plan.header_bytes + plan.entry_bytes;
+    ca.part_ml_prefix = reinterpret_cast<float*>(ws + at); at += plan.ml_prefix_bytes;
+    ca.part_o_prefix = reinterpret_cast<float*>(ws + at);  at += plan.o_prefix_bytes;
+    a.part_ml = reinterpret_cast<float*>(ws + at);         at += plan.ml_bytes;
+    a.part_o = reinterpret_cast<float*>(ws + at);
     a.out = out;
     a.lse = lse;
     a.batch = p->batch;
@@ -486,10 +495,9 @@ int gqa_decode_attn_shared_prefix(const gqa_cascade_params* cp, const void* q, c
 
     int workgroups = workgroups_for(0);
     if (workgroups < 1) return GQA_ERR_LAUNCH;
-    const int per_group = gqa::partial_cascade_workers_per_group();
-    const int64_t max_tiles = (int64_t)p->num_kv_heads *
-        ((int64_t)cp->num_groups * gqa::tiles_of(cp->max_prefix_len) + (int64_t)p->batch * gqa::tiles_of(p->max_kv_len));
-    const int64_t useful = (max_tiles + gqa::kMinShareTiles * per_group - 1) / (gqa::kMinShareTiles * per_group);
+    // no more workgroups than the stream can feed with shares of the minimum cost
+    const int64_t per_group_cost = (int64_t)gqa::cascade_share_cost(0, 0, 1) * gqa::partial_cascade_workers_per_group();
+    const int64_t useful = (plan.max_cost + per_group_cost - 1) / per_group_cost;
     if (useful < workgroups) workgroups = (int)(useful > 0 ? useful : 1);
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (gqa::launch_partial_cascade(ca, workgroups, s) != hipSuccess) return GQA_ERR_LAUNCH;

@@ -186,17 +186,40 @@ __device__ __forceinline__ StreamPos wave_stream_locate(const KernelArgs& a, int
 }
 
 // Device-side view of one shared-prefix ("cascade") call: `base` describes the queries, the
-// per-sequence suffix caches (kv_lens = suffix lengths) and the outputs; the prefix of group j
-// lives at kp + j*kp_stride_g + g*kp_stride_h + t*kp_stride_t.  base.row_prefix holds two arrays
-// of entries + 1 ints (entries = num_groups prefixes, then batch suffixes): the stream position of
-// every entry, then the number of its first row.
+// per-sequence suffix caches (kv_lens = suffix lengths), the outputs and the suffix area of the
+// partial results (16 columns per slot); the prefix of group j lives at
+// kp + j*kp_stride_g + g*kp_stride_h + t*kp_stride_t and its pieces go to the prefix area (32
+// columns per slot).  base.row_prefix holds entries + 1 ints (entries = num_groups prefixes, then
+// batch suffixes): the position of every entry on the cost axis of the stream split.
 constexpr int kCascadeColumns = 64;      // query rows (samples x heads of a KV group) a group may have
+#ifndef GQA_CASCADE_COST_TILE            // cost of a tile with one column block (reading it dominates)
+#define GQA_CASCADE_COST_TILE 8
+#endif
+#ifndef GQA_CASCADE_COST_BLOCK           // cost of every further column block served from the same read
+#define GQA_CASCADE_COST_BLOCK 1
+#endif
+constexpr int kCascadeMaxTileCost = GQA_CASCADE_COST_TILE + GQA_CASCADE_COST_BLOCK;     // two column blocks per read
+__host__ __device__ __forceinline__ int cascade_tile_cost(int nb) {
+    return GQA_CASCADE_COST_TILE + GQA_CASCADE_COST_BLOCK * (nb - 1);
+}
+// Cost units per share: the total cut into equal parts (never below two plain tiles), or a fixed
+// number of plain tiles; in both cases at least the largest tile cost, so that consecutive shares
+// inside a row each own a tile of it.
+__host__ __device__ __forceinline__ int cascade_share_cost(int64_t total, int fixed_tiles, int workers) {
+    int64_t c = fixed_tiles > 0 ? (int64_t)fixed_tiles * GQA_CASCADE_COST_TILE : (total + workers - 1) / workers;
+    const int64_t floor_cost = kMinShareTiles * GQA_CASCADE_COST_TILE > kCascadeMaxTileCost
+                                   ? kMinShareTiles * GQA_CASCADE_COST_TILE : kCascadeMaxTileCost;
+    if (c < floor_cost) c = floor_cost;
+    return (int)c;
+}
 struct CascadeArgs {
     KernelArgs base;
     const uint16_t* kp;
     const uint16_t* vp;
     const int32_t* prefix_lens;      // [num_groups]
     const int32_t* group_start;      // [num_groups + 1], sequences of group j: [group_start[j], group_start[j+1])
+    float* part_ml_prefix;           // [slot][32][2]
+    float* part_o_prefix;            // [slot][32][D]
     int32_t num_groups, max_prefix_len;
     int64_t kp_stride_g, kp_stride_h, kp_stride_t;
     int64_t vp_stride_g, vp_stride_h, vp_stride_t;
