@@ -188,7 +188,9 @@ PROBE_MODES = {0: "non-temporal, 1 KB per load instruction (V path), 1 tile in f
                4: "non-temporal, operand-shaped, 2 tiles in flight",
                5: "non-temporal, 1 KB per load, 2 tiles in flight",
                6: "non-temporal, the kernel's mix: half operand-shaped (K), half 1 KB per load (V), 1 tile in flight",
-               7: "ordinary loads, the kernel's mix, 1 tile in flight"}
+               7: "ordinary loads, the kernel's mix, 1 tile in flight",
+               8: "non-temporal, the kernel's mix, the 4 wavefronts of a workgroup take the tiles of its run in turn",
+               9: "non-temporal, the kernel's mix, all wavefronts take tiles in turn (chip-wide sweep)"}
 
 
 def bench_probe(args) -> int:

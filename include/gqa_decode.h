@@ -373,6 +373,10 @@ int gqa_decode_stream_read(const void* src, size_t bytes, void* sink, int32_t wo
  *   3  as 1 with ordinary (temporal) loads
  *   4  as 1 with two tiles in flight per wavefront (double-buffered)
  *   5  as 0 with two tiles in flight
+ *   6  the attention kernel's own mix: half of each tile as 1, half as 0
+ *   7  as 6 with ordinary loads
+ *   8  as 6, but a workgroup owns a contiguous run and its 4 wavefronts take the tiles in turn
+ *   9  as 6, but all wavefronts take tiles in turn (the whole chip sweeps through memory together)
  * Not part of the attention path; the benchmark's --probe mode times it.
  */
 int gqa_decode_stream_probe(const void* src, size_t bytes, void* sink, int32_t workgroups, int32_t mode, void* stream);

@@ -586,7 +586,7 @@ int gqa_decode_stream_read(const void* src, size_t bytes, void* sink, int32_t wo
 
 int gqa_decode_stream_probe(const void* src, size_t bytes, void* sink, int32_t workgroups, int32_t mode, void* stream) {
     if (!src || !sink || workgroups < 1 || workgroups > 4096 || bytes < 16384 || bytes / 16384 > 0x7fffffffULL ||
-        !aligned16(src) || mode < 0 || mode > 7)
+        !aligned16(src) || mode < 0 || mode > 9)
         return GQA_ERR_INVALID_ARG;
     return gqa::launch_stream_probe(src, bytes, sink, workgroups, mode, static_cast<hipStream_t>(stream)) == hipSuccess
                ? GQA_OK : GQA_ERR_LAUNCH;

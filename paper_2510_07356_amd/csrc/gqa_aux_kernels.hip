@@ -172,12 +172,40 @@ __device__ __forceinline__ u32x4 probe_consume(u32x4 (&r)[16], u32x4* lds_wave, 
     return acc;
 }
 
-template <int PATTERN, bool NT, int TILES>
+// INTERLEAVE 0: every wavefront owns a contiguous run of tiles.  1: a workgroup owns a contiguous run and
+// its 4 wavefronts take the tiles of it in turn.  2: all wavefronts take tiles in turn (the whole chip
+// sweeps through memory together).
+template <int PATTERN, bool NT, int TILES, int INTERLEAVE = 0>
 __global__ __launch_bounds__(256, 1) void stream_probe_kernel(const u32x4* __restrict__ src, int n_tiles,
                                                               uint32_t* __restrict__ sink) {
     extern __shared__ u32x4 probe_lds[];                 // PATTERN 2: 16 KB per wavefront
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int worker = blockIdx.x * 4 + wave, workers = gridDim.x * 4;
+    if (INTERLEAVE != 0) {
+        // tile index of step k: base + k * step, for k < count
+        int base, step, count;
+        if (INTERLEAVE == 1) {
+            const int per_group = (n_tiles + (int)gridDim.x - 1) / (int)gridDim.x;
+            const int g0 = min((int)blockIdx.x * per_group, n_tiles), g1 = min(g0 + per_group, n_tiles);
+            base = g0 + wave; step = 4; count = (g1 - base + 3) / 4;
+        } else {
+            base = worker; step = workers; count = (n_tiles - base + workers - 1) / workers;
+        }
+        u32x4 acc = {0, 0, 0, 0};
+        u32x4 ra[16];
+        if (count > 0) {
+            probe_request<PATTERN, NT>(src + (size_t)base * 1024, lane, ra);
+            for (int k = 0; k < count; ++k) {
+                acc ^= probe_consume<PATTERN>(ra, probe_lds, lane);
+                probe_request<PATTERN, NT>(src + (size_t)(base + min(k + 1, count - 1) * step) * 1024, lane, ra);
+            }
+            acc ^= probe_consume<PATTERN>(ra, probe_lds, lane);
+        }
+        uint32_t x = acc.x ^ acc.y ^ acc.z ^ acc.w;
+        for (int o = 32; o > 0; o >>= 1) x ^= __shfl_xor(x, o);
+        if (lane == 0) sink[worker] = x;
+        return;
+    }
     const int share = (n_tiles + workers - 1) / workers;
     const int first = min(worker * share, n_tiles), last = min(first + share, n_tiles);
     u32x4* lds_wave = probe_lds + (PATTERN == 2 ? wave * 1024 : 0);
@@ -219,6 +247,8 @@ hipError_t launch_stream_probe(const void* src, size_t bytes, void* sink, int wo
         case 5: hipLaunchKernelGGL((stream_probe_kernel<0, true, 2>), g, b, 0, s, p, n_tiles, k); break;
         case 6: hipLaunchKernelGGL((stream_probe_kernel<3, true, 1>), g, b, 0, s, p, n_tiles, k); break;
         case 7: hipLaunchKernelGGL((stream_probe_kernel<3, false, 1>), g, b, 0, s, p, n_tiles, k); break;
+        case 8: hipLaunchKernelGGL((stream_probe_kernel<3, true, 1, 1>), g, b, 0, s, p, n_tiles, k); break;
+        case 9: hipLaunchKernelGGL((stream_probe_kernel<3, true, 1, 2>), g, b, 0, s, p, n_tiles, k); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
