@@ -7,12 +7,12 @@
 //
 // Decomposition.  One workgroup (8 wavefronts, two per SIMD) owns 256 consecutive query rows of one
 // query head, 32 rows per wavefront, and walks the key/value tokens 0 .. (last row) in tiles of 128.
-// A K tile is staged in LDS row-major, a V tile transposed ([column][token], transposed in registers
-// with v_perm_b32 on the way in; inside a V^T row the 4-token groups of column block dt sit at
-// position group ^ 2 dt, which makes the transposed 8-byte stores bank-conflict free), both
-// double-buffered with one barrier per tile.  The two halves of the next tile travel in turn, so
-// that only one of them holds registers: K is requested at the start of a tile and stored after its
-// second 32-token step, V is requested then and stored at the end.
+// K and V tiles are staged in LDS row-major (K rows of 272 bytes, V rows of 320 bytes: the paddings
+// that make the fragment reads bank-conflict free), both double-buffered with one barrier per tile.
+// V^T fragments come out of the transposing LDS load ds_read_b64_tr_b16, which hands every lane four
+// consecutive tokens of one column, so V is never transposed in registers.  The two halves of the
+// next tile travel in turn, so that only one of them holds registers: K is requested at the start of
+// a tile and stored after its second 32-token step, V is requested then and stored at the end.
 //
 // LDS fragments are requested ahead of the matrix instructions that use them: the V^T fragments of
 // a 32-token step and the K fragments of the next step are requested right after the step's score
@@ -42,15 +42,16 @@ namespace {
 using namespace tile;
 
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef short v4i16 __attribute__((ext_vector_type(4)));
 
 constexpr int kBM = 256;               // query rows per workgroup
 constexpr int kWaveRows = 32;          // query rows per wavefront (one MFMA column block)
 constexpr int kPrefillThreads = 64 * (kBM / kWaveRows);
 constexpr int kBN = 128;               // key tokens per LDS tile
 constexpr int kKStride = kHeadDim + 8; // bf16 elements per K row in LDS (272 B: conflict-free b128 reads)
-constexpr int kVStride = kBN + 4;      // bf16 elements per V^T row in LDS (136 B: conflict-free b64 reads)
+constexpr int kVStride = kHeadDim + 32; // bf16 elements per V row in LDS (320 B: the 8 rows x 64 B a transposing read touches fall in distinct banks; measured full rate, 288 B half)
 constexpr int kKTile = kBN * kKStride;         // elements
-constexpr int kVTile = kHeadDim * kVStride;    // elements
+constexpr int kVTile = kBN * kVStride;         // elements
 
 __device__ __forceinline__ f32x16 mfma32(const uint4& a, const uint4& b, const f32x16& c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b),
@@ -69,6 +70,13 @@ __device__ __forceinline__ float max_across_halves(float x) {
     const unsigned u = __builtin_bit_cast(unsigned, x);
     const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
     return fmaxf(__builtin_bit_cast(float, (unsigned)r[0]), __builtin_bit_cast(float, (unsigned)r[1]));
+}
+
+// 8 bytes of LDS through the transposing load: within each group of 16 lanes, result lane j receives
+// element j % 4 of the 8-byte pieces addressed by lanes j / 4, 4 + j / 4, 8 + j / 4, 12 + j / 4
+__device__ __forceinline__ uint2 lds_read_tr(const uint16_t* p) {
+    const v4i16 r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4i16*)p);
+    return __builtin_bit_cast(uint2, r);
 }
 
 // One K (V) tile on its way from global memory to LDS, per thread.  The two halves are staged in
@@ -127,23 +135,10 @@ __device__ __forceinline__ void store_k_tile(const StagingK& st, uint16_t* ks) {
 __device__ __forceinline__ void store_v_tile(const StagingV& st, uint16_t* vs) {
     const int tid = threadIdx.x;
     const int piece = tid & 15, grp = tid >> 4;
-    // 4 tokens x 8 columns -> 8 columns x 4 tokens, then one 8-byte store per column.  Within a V^T row
-    // the 4-token groups of column block dt = column / 32 sit at position group ^ 2 dt: the 16 column
-    // pieces a wavefront writes at once then fall into distinct banks.
-    const int slot = grp ^ (2 * (piece >> 2));
-    auto column_pair = [&](uint32_t t0, uint32_t t1, uint32_t t2, uint32_t t3, int pr) {
-        uint2 even, odd;                                                  // columns 2 pr and 2 pr + 1, tokens 0..3
-        even.x = __builtin_amdgcn_perm(t1, t0, 0x05040100u);
-        even.y = __builtin_amdgcn_perm(t3, t2, 0x05040100u);
-        odd.x = __builtin_amdgcn_perm(t1, t0, 0x07060302u);
-        odd.y = __builtin_amdgcn_perm(t3, t2, 0x07060302u);
-        *reinterpret_cast<uint2*>(vs + (8 * piece + 2 * pr) * kVStride + 4 * slot) = even;
-        *reinterpret_cast<uint2*>(vs + (8 * piece + 2 * pr + 1) * kVStride + 4 * slot) = odd;
-    };
-    column_pair(st.r0.x, st.r1.x, st.r2.x, st.r3.x, 0);
-    column_pair(st.r0.y, st.r1.y, st.r2.y, st.r3.y, 1);
-    column_pair(st.r0.z, st.r1.z, st.r2.z, st.r3.z, 2);
-    column_pair(st.r0.w, st.r1.w, st.r2.w, st.r3.w, 3);
+    *reinterpret_cast<uint4*>(vs + (4 * grp + 0) * kVStride + 8 * piece) = st.r0;
+    *reinterpret_cast<uint4*>(vs + (4 * grp + 1) * kVStride + 8 * piece) = st.r1;
+    *reinterpret_cast<uint4*>(vs + (4 * grp + 2) * kVStride + 8 * piece) = st.r2;
+    *reinterpret_cast<uint4*>(vs + (4 * grp + 3) * kVStride + 8 * piece) = st.r3;
 }
 
 __global__ __launch_bounds__(kPrefillThreads, 1) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefill_kernel(PrefillArgs a) {
@@ -197,6 +192,10 @@ __global__ __launch_bounds__(kPrefillThreads, 1) __attribute__((amdgpu_waves_per
         for (int r = 0; r < 16; ++r) acc[dt][r] = 0.f;
     float m = -INFINITY, l = 0.f;          // running maximum of the raw scores (times |scale| log2 e in the exponent)
     const int qrow = q0 + n;
+    // this lane's source piece of the transposing V reads: token row 4 kb + e (e = (lane % 16) / 4), columns
+    // 16 ((lane / 16) % 2) + 4 (lane % 4) of a 32-column block; the 16 lanes of a group then receive columns
+    // 0..15 of that half, four consecutive tokens each
+    const int v_lane = (4 * kb + ((lane & 15) >> 2)) * kVStride + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
 
     const int kv_end = min(qb * kBM + kBM, len);        // keys this workgroup needs: [0, kv_end)
     // a block beyond the end of its sequence stages one tile, walks none and writes nothing (leaving the
@@ -244,9 +243,9 @@ __global__ __launch_bounds__(kPrefillThreads, 1) __attribute__((amdgpu_waves_per
             for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
                 for (int ks2 = 0; ks2 < 2; ++ks2) {
-                    const uint16_t* vp = vs + (32 * dt + n) * kVStride + 32 * tt + 4 * (((4 * ks2) ^ (2 * dt)) + kb);
-                    vf[4 * dt + 2 * ks2] = *reinterpret_cast<const uint2*>(vp);
-                    vf[4 * dt + 2 * ks2 + 1] = *reinterpret_cast<const uint2*>(vp + ((dt & 1) ? -8 : 8));
+                    const uint16_t* vp = vs + v_lane + (32 * tt + 16 * ks2) * kVStride + 32 * dt;
+                    vf[4 * dt + 2 * ks2] = lds_read_tr(vp);                         // tokens 16 ks2 + 4 kb + 0..3
+                    vf[4 * dt + 2 * ks2 + 1] = lds_read_tr(vp + 8 * kVStride);      // tokens 16 ks2 + 8 + 4 kb + 0..3
                 }
             {
                 const int tn = min(tt + 1, kBN / 32 - 1);
@@ -258,11 +257,14 @@ __global__ __launch_bounds__(kPrefillThreads, 1) __attribute__((amdgpu_waves_per
             // online softmax on the raw scores (the scale is folded into the exponent: 2^(s c - m c));
             // only tiles that touch the diagonal pay for the mask
             const bool diagonal = tok0 + 31 > q0;             // some (token, row) pair of this tile is masked
-            const int ahead = tok0 + 4 * kb - qrow;           // register r holds token qrow + ahead + 8 (r / 4) + r % 4
+            unsigned hidden = 0;                              // bit r: register r holds a token beyond this lane's row
             if (diagonal) {
+                const int ahead = tok0 + 4 * kb - qrow;       // register r holds token qrow + ahead + 8 (r / 4) + r % 4
+#pragma unroll
+                for (int r = 0; r < 16; ++r) hidden |= (ahead + 8 * (r >> 2) + (r & 3) > 0 ? 1u : 0u) << r;
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
-                    if (ahead + 8 * (r >> 2) + (r & 3) > 0) sc[r] = -INFINITY;
+                    if ((hidden >> r) & 1u) sc[r] = -INFINITY;
             }
             float tmax = sc[0];
 #pragma unroll
@@ -284,7 +286,7 @@ __global__ __launch_bounds__(kPrefillThreads, 1) __attribute__((amdgpu_waves_per
             if (diagonal) {                                   // also covers a zero scale, where -inf * 0 is not a number
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
-                    if (ahead + 8 * (r >> 2) + (r & 3) > 0) p[r] = 0.f;
+                    if ((hidden >> r) & 1u) p[r] = 0.f;
             }
             uint4 pb[2];                                      // P^T operands of the two k-steps
 #pragma unroll
