@@ -21,7 +21,8 @@
 // Per wavefront and 32 tokens (v_mfma_f32_32x32x16_bf16; lane l: n = l % 32, kb = l / 32;
 // A[m][8kb+e], B[8kb+e][n], D[8(r/4) + 4kb + r%4][n] in register r):
 //   S^T[tok, q]  = K Q^T      A = K rows from LDS, B = Q^T kept in registers for the whole kernel
-//   online softmax per query row (= per lane column), base-2 exponentials, P rounded to bf16
+//   online softmax per query row (= per lane column), base-2 exponentials, P rounded to bf16; the
+//                             accumulators are rescaled only when a score exceeds the reference by 2^8
 //   O^T[d, q]   += V^T P^T    A = V^T from LDS, B = P^T: with contraction slot (kb, e) of step s
 //                             standing for token 16s + 4kb + e (e < 4) or 16s + 8 + 4kb + e - 4,
 //                             the D registers 8s .. 8s+7 of S^T are exactly the B operand, so P
@@ -50,6 +51,7 @@ constexpr int kPrefillThreads = 64 * (kBM / kWaveRows);
 constexpr int kBN = 128;               // key tokens per LDS tile
 constexpr int kKStride = kHeadDim + 8; // bf16 elements per K row in LDS (272 B: conflict-free b128 reads)
 constexpr int kVStride = kHeadDim + 32; // bf16 elements per V row in LDS (320 B: the 8 rows x 64 B a transposing read touches fall in distinct banks; measured full rate, 288 B half)
+constexpr float kSlack = 8.f;             // log2 of the largest softmax weight before the accumulators are rescaled
 constexpr int kKTile = kBN * kKStride;         // elements
 constexpr int kVTile = kBN * kVStride;         // elements
 
@@ -190,7 +192,7 @@ __global__ __launch_bounds__(kPrefillThreads, 1) __attribute__((amdgpu_waves_per
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[dt][r] = 0.f;
-    float m = -INFINITY, l = 0.f;          // running maximum of the raw scores (times |scale| log2 e in the exponent)
+    float m = -INFINITY, l = 0.f;          // reference of the exponents, a raw score within 2^kSlack of the running maximum (times |scale| log2 e in the exponent)
     const int qrow = q0 + n;
     // this lane's source piece of the transposing V reads: token row 4 kb + e (e = (lane % 16) / 4), columns
     // 16 ((lane / 16) % 2) + 4 (lane % 4) of a 32-column block; the 16 lanes of a group then receive columns
@@ -239,11 +241,13 @@ __global__ __launch_bounds__(kPrefillThreads, 1) __attribute__((amdgpu_waves_per
             __builtin_amdgcn_sched_barrier(0);
             // requests that do not depend on the softmax: V^T of this tile, K of the next one
             uint2 vf[16];
+            int v_step = v_lane + 32 * tt * kVStride;         // one base register per step; the rest are immediates
+            asm volatile("" : "+v"(v_step));
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
                 for (int ks2 = 0; ks2 < 2; ++ks2) {
-                    const uint16_t* vp = vs + v_lane + (32 * tt + 16 * ks2) * kVStride + 32 * dt;
+                    const uint16_t* vp = vs + v_step + 16 * ks2 * kVStride + 32 * dt;
                     vf[4 * dt + 2 * ks2] = lds_read_tr(vp);                         // tokens 16 ks2 + 4 kb + 0..3
                     vf[4 * dt + 2 * ks2 + 1] = lds_read_tr(vp + 8 * kVStride);      // tokens 16 ks2 + 8 + 4 kb + 0..3
                 }
@@ -271,7 +275,9 @@ __global__ __launch_bounds__(kPrefillThreads, 1) __attribute__((amdgpu_waves_per
             for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, sc[r]);
             tmax = max_across_halves(tmax);
             const float mn = fmaxf(m, tmax);                  // finite: token 0 is visible to every row
-            if (__builtin_amdgcn_ballot_w64(mn > m) != 0) {
+            // the reference m only has to stay within 2^kSlack of the true maximum: weights up to 2^kSlack are
+            // as exact in bf16 and fp32 as weights up to 1, and the accumulators are rescaled far less often
+            if (__builtin_amdgcn_ballot_w64(!((tmax - m) * c <= kSlack)) != 0) {   // also the first step (m = -inf), whatever c
                 // first tile: nothing accumulated yet (and -inf * 0 would not be a number for a zero scale)
                 const float alpha = m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((m - mn) * c);
                 l *= alpha;
