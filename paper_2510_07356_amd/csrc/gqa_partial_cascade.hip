@@ -407,30 +407,49 @@ __global__ __launch_bounds__(256) void combine_cascade_kernel(CascadeArgs ca) {
     const int32_t* __restrict__ gs = ca.group_start;
     const int32_t* __restrict__ pre = a.row_prefix;                 // position of every entry on the cost axis
     const int share_cost = a.header[1];
-    // the last group j with gs[j] <= b (the one holding b): gs rises, so the lanes whose entry is <= b
-    // form a prefix of the list and one ballot per 64 groups counts them
-    int count = 0;
-    for (int base = 0; base < ca.num_groups; base += 64) {
-        const int idx = base + lane;
-        const int v = idx < ca.num_groups ? gs[idx] : 0x7fffffff;
-        count += __builtin_popcountll(__builtin_amdgcn_ballot_w64(v <= b));
+    // Everything the row needs to know about its group and its sequence is requested at once, so that the
+    // wavefront waits for one round trip before it asks for the pieces: lane i holds group i's start, prefix
+    // length and position on the cost axis, and the group of b is picked out of the lanes afterwards.
+    // The last group j with gs[j] <= b holds b: gs rises, so the lanes whose entry is <= b form a prefix.
+    const int e = ca.num_groups + b;
+    const int pre_e = pre[e];
+    const int len_b = clamped_len(a, b);
+    int j, g0, g1, plen_j, pre_j;
+    if (ca.num_groups < 64) {
+        const int ig = min(lane, ca.num_groups - 1);
+        const int v = gs[min(lane, ca.num_groups)];          // gs has num_groups + 1 entries
+        const int pl = ca.prefix_lens[ig];
+        const int pj = pre[ig];
+        const int count = __builtin_popcountll(__builtin_amdgcn_ballot_w64(lane < ca.num_groups && v <= b));
+        j = max(count - 1, 0);
+        g0 = __shfl(v, j); g1 = __shfl(v, j + 1);
+        plen_j = __shfl(pl, j); pre_j = __shfl(pj, j);
+    } else {
+        int count = 0;
+        for (int base = 0; base < ca.num_groups; base += 64) {
+            const int idx = base + lane;
+            const int v = idx < ca.num_groups ? gs[idx] : 0x7fffffff;
+            count += __builtin_popcountll(__builtin_amdgcn_ballot_w64(v <= b));
+        }
+        j = max(count - 1, 0);
+        g0 = gs[j]; g1 = gs[j + 1];
+        plen_j = ca.prefix_lens[j]; pre_j = pre[j];
     }
-    const int j = max(count - 1, 0);
     // pieces of the prefix row (group j, g, read f / 32), then of b's suffix row g
     RowPieces rp[2];
     {
-        const EntryShape s = entry_shape<false>(ca, j);
-        const int g0 = gs[j], g1 = gs[j + 1];
+        const int m = max(g1 - g0, 0);                       // the shape of entry j, as entry_shape computes it
+        const int cols = min(m * G, kCascadeColumns);
+        const int plen = m > 0 ? min(max(plen_j, 0), ca.max_prefix_len) : 0;
         const int f = (b - g0) * G + hh;
         const bool served = g0 <= b && b < g1 && f < kCascadeColumns;
-        const int tiles = served ? tiles_of(s.len) : 0, r = (f >> 5) & 1;
-        const int w = cascade_tile_cost(blocks_of_read(s.cols, r));
-        const int row_start = pre[j] + g * tiles * head_tile_cost(s.cols) + r * tiles * cascade_tile_cost(blocks_of_read(s.cols, 0));
+        const int tiles = served ? tiles_of(plen) : 0, r = (f >> 5) & 1;
+        const int w = cascade_tile_cost(blocks_of_read(cols, r));
+        const int row_start = pre_j + g * tiles * head_tile_cost(cols) + r * tiles * cascade_tile_cost(blocks_of_read(cols, 0));
         rp[0] = row_pieces(ca.part_ml_prefix, ca.part_o_prefix, row_start, tiles, w, share_cost,
                            2 * (j * a.num_kv_heads + g) + r, 32, f & 31);
-        const int e = ca.num_groups + b;
-        const int ws = cascade_tile_cost(1), stiles = tiles_of(clamped_len(a, b));
-        rp[1] = row_pieces(a.part_ml, a.part_o, pre[e] + g * stiles * ws, stiles, ws, share_cost, b * a.num_kv_heads + g, 16, hh);
+        const int ws = cascade_tile_cost(1), stiles = tiles_of(len_b);
+        rp[1] = row_pieces(a.part_ml, a.part_o, pre_e + g * stiles * ws, stiles, ws, share_cost, b * a.num_kv_heads + g, 16, hh);
     }
     // one list of n pieces, merged in order with a running maximum, eight at a time so that their
     // loads are in flight together (prefix and suffix pieces in the same batch)
