@@ -99,6 +99,20 @@ def test_groups_without_sequences(binding, paged):
         check(sw, *binding.run_shared_prefix(sw, chunk_tokens=chunk), f"casc_holes/paged{int(paged)}/c{chunk}")
 
 
+@pytest.mark.parametrize("groups", [63, 64, 65, 150])
+def test_many_groups(binding, groups):
+    """More groups than a wavefront has lanes: the search for a sequence's group then takes several
+    rounds of 64 (63 is the largest list the combine kernel handles in one)."""
+    rng = np.random.default_rng(groups)
+    sizes = rng.integers(0, 4, size=groups)
+    sizes[0], sizes[-1] = 2, 1
+    prefixes = rng.integers(0, 200, size=groups)
+    suffixes = rng.integers(0, 150, size=int(sizes.sum()))
+    sw = wl.make_shared_prefix(f"casc_many{groups}", 306 + groups, list(sizes), list(prefixes), list(suffixes),
+                               paged=bool(groups % 2))
+    check(sw, *binding.run_shared_prefix(sw), f"casc_many{groups}")
+
+
 def test_too_large_group_is_rejected(binding):
     sw = wl.make_shared_prefix("casc_big", 303, [13], [64], [10] * 13)       # 13 * 5 = 65 query rows > 64
     with pytest.raises(binding.GqaError) as e:
