@@ -162,6 +162,7 @@ __global__ __launch_bounds__(kPrefillThreads, 1) __attribute__((amdgpu_waves_per
     // tokens of this sequence; a.seq_len is the padded length the tensors and the grid are laid out for
     const int len = a.seq_lens != nullptr ? min(max(uniform_i32(a.seq_lens, b), 0), a.seq_len) : a.seq_len;
     const int h = g * G + hh;
+    if (qb * kBM >= len) return;                              // a row block beyond the end of its sequence (whole workgroup)
 
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n = lane & 31, kb = lane >> 5;
@@ -200,9 +201,7 @@ __global__ __launch_bounds__(kPrefillThreads, 1) __attribute__((amdgpu_waves_per
     const int v_lane = (4 * kb + ((lane & 15) >> 2)) * kVStride + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
 
     const int kv_end = min(qb * kBM + kBM, len);        // keys this workgroup needs: [0, kv_end)
-    // a block beyond the end of its sequence stages one tile, walks none and writes nothing (leaving the
-    // kernel early instead costs the other blocks 2 % in the code the compiler then lays out)
-    const int n_tiles = qb * kBM < len ? (kv_end + kBN - 1) / kBN : 0;
+    const int n_tiles = (kv_end + kBN - 1) / kBN;
 
     {
         StagingK k0;
