@@ -314,6 +314,21 @@ def bench_decode_step(args) -> int:
     return 0
 
 
+def host_cpu_description() -> str:
+    """Model name of the host processor, the cores this process may run on and the cores the machine has."""
+    model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    allowed = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else os.cpu_count()
+    return f"{model}; {allowed} of {os.cpu_count()} cores available to this process"
+
+
 def run_decode_config(index, steps, warmup, args, with_cpu=True, with_stream_read=False, events_every=EVENT_STRIDE):
     """Times gqa_decode_attn on one named configuration.  Returns (summary dict, details dict): the
     summary is the per-configuration entry of the JSON line, the details feed the headline keys."""
@@ -602,6 +617,8 @@ def main() -> int:
             "sample": f"the whole workload ({w.batch} sequences, {w.kv_tokens} KV tokens), mean of {d['reps']} runs, "
                       f"{d['t_cpu']:.3f} s wall each on {d['ref_threads']} threads; one run on a single thread: {t_one:.2f} s",
             "single_thread_value": round(kv_bytes / t_one / 1e12, 6),
+            "gpu_over_cpu": round(d["t_cpu"] / (d["ms_per_step"] * 1e-3), 1),
+            "host": host_cpu_description(),
         }
         result["parity"] = summary["parity"]
 

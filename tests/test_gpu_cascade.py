@@ -128,3 +128,38 @@ def test_sampling_batch_full_size(binding):
     sw10 = wl.make_sampling_batch(seed=6, tasks=6, samples=10)
     out, lse = binding.run_shared_prefix(sw10)
     check(sw10, out, lse, "sampling_6x10")
+
+
+def random_cascade_case(rng):
+    hkv = int(rng.choice([1, 2, 3, 8]))
+    group = int(rng.choice([1, 2, 4, 5, 8, 16]))
+    n_groups = int(rng.choice([1, 2, 7, 20, 70]))
+    most = max(64 // group, 1)                                   # a group serves at most 64 query rows
+    sizes = rng.integers(0, min(most, 12) + 1, size=n_groups)
+    if sizes.sum() == 0:
+        sizes[0] = 1
+    top_p = int(rng.choice([0, 40, 700, 3000]))
+    top_s = int(rng.choice([40, 300, 2000]))
+    prefixes = rng.integers(0, top_p + 1, size=n_groups)
+    suffixes = rng.integers(0, top_s + 1, size=int(sizes.sum()))
+    kind = rng.random(len(suffixes))
+    suffixes = np.where(kind < 0.15, 0, np.where(kind < 0.25, 1, suffixes))
+    return dict(hkv=hkv, group=group, sizes=sizes, prefixes=prefixes, suffixes=suffixes,
+                paged=bool(rng.random() < 0.5), layout=str(rng.choice(["head_major", "token_major"])),
+                chunk=int(rng.choice([0, 0, 32, 96, 512])),
+                scale=float(rng.choice([1.0 / np.sqrt(128), 0.25, -0.05])))
+
+
+@pytest.mark.parametrize("seed", list(range(16)))
+def test_random_shared_prefix_shape(binding, seed):
+    """Seeded random group counts and sizes (groups without sequences, up to 64 query rows per group), prefix
+    and suffix lengths (empty ones, single tokens), head counts, layouts, paging, fixed and automatic splits."""
+    rng = np.random.Generator(np.random.PCG64([901, seed]))
+    c = random_cascade_case(rng)
+    print(f"seed={seed} Hkv={c['hkv']} G={c['group']} groups={len(c['sizes'])} B={int(c['sizes'].sum())} "
+          f"prefix[max]={int(c['prefixes'].max())} suffix[max]={int(c['suffixes'].max(initial=0))} paged={c['paged']} "
+          f"layout={c['layout']} chunk={c['chunk']} scale={c['scale']:.4f}", flush=True)
+    sw = wl.make_shared_prefix(f"casc_rand{seed}", 2000 + seed, list(c["sizes"]), list(c["prefixes"]),
+                               list(c["suffixes"]), num_q_heads=c["hkv"] * c["group"], num_kv_heads=c["hkv"],
+                               paged=c["paged"], layout=c["layout"], scale=c["scale"])
+    check(sw, *binding.run_shared_prefix(sw, chunk_tokens=c["chunk"]), f"casc_rand{seed}")
