@@ -93,6 +93,25 @@ def test_outlier_keys_move_the_running_maximum(binding):
     check_rows(out, lse, oracle_rows(q, k, v, 0, rows, scale), 0, rows, "prefill_outliers")
 
 
+@pytest.mark.parametrize("growth", [1.0, 4.0, 11.0])
+def test_scores_that_keep_growing_along_the_sequence(binding, growth):
+    """Keys aligned with the queries and growing with the token index: the largest score of a row rises by
+    `growth` binary orders of magnitude per 32 tokens, so the exponent reference of the online softmax lags
+    behind the maximum (weights above 1 for growth 1 and 4) or has to follow it at every step (growth 11)."""
+    scale = float(np.float32(1.0 / np.sqrt(128)))
+    T = 700
+    rng = np.random.default_rng(457)
+    u = rng.standard_normal(128).astype(np.float32)
+    per_token = growth / 32.0 / (scale * np.log2(np.e)) / float(u @ u)      # raw score rises by this per token
+    q = wl.f32_to_bf16_bits(np.broadcast_to(u, (1, T, 10, 128)) + 0.1 * rng.standard_normal((1, T, 10, 128), dtype=np.float32))
+    ramp = (np.arange(T, dtype=np.float32) * per_token)[None, :, None, None] * u
+    k = wl.f32_to_bf16_bits(ramp + 0.1 * rng.standard_normal((1, T, 2, 128), dtype=np.float32))
+    v = wl.f32_to_bf16_bits(rng.standard_normal((1, T, 2, 128), dtype=np.float32))
+    out, lse = run(binding, q, k, v, scale)
+    rows = np.arange(T)
+    check_rows(out, lse, oracle_rows(q, k, v, 0, rows, scale), 0, rows, f"prefill_growing_{growth}")
+
+
 def test_strided_inputs_and_group_sizes(binding):
     """Token-major projections sliced out of a fused QKV buffer, group sizes 1, 4 and 16."""
     import torch
